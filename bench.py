@@ -1,0 +1,117 @@
+#!/usr/bin/env python3
+"""Throughput of the EGTP hot path on one MI355X.
+
+One step = one pass of the whole path over one ragged batch already resident in HBM:
+offsets from lengths, fused LM-head + entropy (Eq. 2), entropy-softmax pooling (Eq. 3-4) and the
+prediction head.  Prints ONE JSON line with tokens scored per second, the roofline figure of
+the dominant kernel (fused LM-head + entropy, priced at 2*d*V FLOP per token against the dense
+bf16 matrix-core peak) and the fp64 oracle timed on this machine's host cores on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="serving", choices=["serving", "mid"])
+    ap.add_argument("--oracle-tokens", type=int, default=256, help="tokens of the CPU-baseline sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU; this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2602_11812_amd import binding as gpu
+    from paper_2602_11812_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    spec = wl.SPECS[args.workload]
+    t0 = time.time()
+    w = wl.make(spec)
+    T, B = w.T, spec.B
+    print(f"[bench] generated {args.workload}: B={B} T={T} d={spec.d} V={spec.V} in {time.time() - t0:.1f}s",
+          file=sys.stderr, flush=True)
+
+    td = gpu.to_device
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    hidden = td(w.hidden)
+    lengths = torch.from_numpy(w.lengths).cuda()
+    offsets = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    out = dict(entropy=torch.empty(T, dtype=torch.float32, device="cuda"),
+               pooled=torch.empty(B, spec.d, dtype=torch.float32, device="cuda"),
+               lse=torch.empty(B, dtype=torch.float32, device="cuda"),
+               pred=torch.empty(B, dtype=torch.float32, device="cuda"))
+    ws = sc.workspace(T, B)
+
+    def step():
+        gpu.egtp_build_offsets(sc.ctx, lengths, B, offsets, None, T)
+        gpu.egtp_score(sc.ctx, hidden, offsets, None, B, T, ws, out["entropy"], out["pooled"], out["lse"], out["pred"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    gpu.egtp_profile_enable(sc.ctx, True, max(1, min(1024, args.steps)))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k1_ms = gpu.egtp_profile_read(sc.ctx)
+    gpu.egtp_profile_enable(sc.ctx, False)
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = T * args.steps / dt
+    k1_avg_s = float(k1_ms.mean()) * 1e-3
+    flops_per_launch = 2.0 * spec.d * spec.V * T          # algorithmic: 2*d*V per token
+    achieved = flops_per_launch / k1_avg_s / 1e12
+
+    cpu = None
+    if args.oracle_tokens > 0:
+        import oracle
+        n = min(args.oracle_tokens, T)
+        off_full = np.concatenate([[0], np.cumsum(w.lengths)]).astype(np.int64)
+        sub_off = np.minimum(off_full, n)
+        keep = int(np.searchsorted(off_full, n, side="left"))
+        sub_off = sub_off[:keep + 1].astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.egtp(w.hidden[:n], sub_off, w.w_lm, oracle.Head(w.w1, w.w2))
+        cdt = time.perf_counter() - t0
+        cpu = {"value": n / cdt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {n} tokens ({keep} sequences, the last truncated) of the same batch, full d and V, "
+                         f"{cdt:.1f}s"}
+
+    line = {
+        "metric": "tokens scored/sec (EGTP prefill, d=4096 V=151936) + % bf16 MFMA peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: EGTP prefill, {B} ragged sequences, {T} tokens, d={spec.d}, "
+                               f"V={spec.V}, head {spec.d}->{spec.d_h}->1, seed {spec.seed}",
+                   "B": B, "T": T, "d": spec.d, "V": spec.V, "d_h": spec.d_h},
+        "pct_bf16_mfma_peak_whole_step": 100.0 * flops_per_launch / (ms_per_step * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+        "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
+                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,162 @@
+/*
+ * egtp.h -- C ABI of the MI355X (gfx950) library for Entropy-Guided Token Pooling (EGTP)
+ * and Progressive Length Prediction (PLP) scoring.
+ *
+ * What the calls compute (paper, Section 3):
+ *   Eq. 2   per-token entropy H_i (nats) of softmax(W_lm h_i) over the full vocabulary;
+ *   Eq. 3   per-sequence weights  w_i = exp(H_i/alpha) / sum_j exp(H_j/alpha)  (alpha = 1 is
+ *           the equation as printed; the text mentions a temperature without placing it);
+ *   Eq. 4   pooled vector  h = sum_i w_i h_i ;
+ *   Sec 3.2 prediction head on h: a perceptron d -> d_h (ReLU) -> n_out.  n_out == 1 gives the
+ *           length directly; n_out == K > 1 applies Eq. 6 (softmax over K bins, expected value
+ *           over the caller's bin centres);
+ *   Eq. 8   PLP: the same head (or a second one) on a representation that aggregates the prompt
+ *           with every token generated so far.  Aggregation here is the running entropy-weighted
+ *           pool, carried as the pair (pooled, lse): folding tokens into that pair gives exactly
+ *           the EGTP pooling of the prompt followed by the generated tokens.
+ *
+ * Conventions
+ *   - Pointers named *_dev / hidden / w_lm / head weights / outputs / workspace / state are HIP
+ *     device pointers on the device that was current at egtp_create; *_host are host pointers.
+ *   - Every pointer is borrowed.  egtp_score / plp_step / egtp_build_offsets allocate nothing:
+ *     the caller brings a workspace of egtp_workspace_bytes().  They only enqueue work on the
+ *     given stream (a hipStream_t passed as void*, NULL = default stream) and return; outputs are
+ *     valid once the stream has been synchronised.  The workspace must not be shared by calls
+ *     that may overlap in time.
+ *   - Matrices are row-major, dense.  hidden is [T x d], w_lm is [vocab x d], both of
+ *     egtp_config.dtype (bf16 = upper half of an fp32, or fp32).  Accumulation, entropies,
+ *     pooled vectors, lse and predictions are fp32.  Row starts must be 16-byte aligned
+ *     (bf16: d a multiple of 8; fp32: d a multiple of 4).
+ *   - Ragged batches: offsets[B+1] int32, offsets[0] = 0, non-decreasing, offsets[B] = T.
+ *     A repeated offset is an empty sequence: pooled = 0, lse = -inf, prediction = head(0).
+ *   - Errors are return codes; on any error nothing has been launched.  B == 0 or T == 0 with
+ *     B == 0 is EGTP_OK and launches nothing.  NaN/Inf inputs are not screened.
+ *   - Results are deterministic: no floating-point atomics, fixed reduction orders.
+ *   - A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef EGTP_H
+#define EGTP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct egtp_ctx egtp_ctx; /* opaque */
+
+typedef enum {
+    EGTP_OK = 0,
+    EGTP_ERR_NULL = 1,      /* a required pointer is NULL */
+    EGTP_ERR_SHAPE = 2,     /* a size is negative, zero where it may not be, or unsupported */
+    EGTP_ERR_OFFSETS = 3,   /* host offsets mirror is malformed */
+    EGTP_ERR_DTYPE = 4,     /* unknown storage type */
+    EGTP_ERR_WORKSPACE = 5, /* workspace NULL, misaligned (256 B) or too small */
+    EGTP_ERR_ARCH = 6,      /* current device is not gfx950 */
+    EGTP_ERR_HIP = 7,       /* a HIP call failed; see egtp_last_hip_error */
+    EGTP_ERR_ALPHA = 8      /* temperature not a finite number > 0 */
+} egtp_status;
+
+typedef enum { EGTP_F32 = 0, EGTP_BF16 = 1 } egtp_dtype;
+
+/* Pooling alternatives of the paper's ablation (Table 3). */
+typedef enum { EGTP_POOL_AVERAGE = 0, EGTP_POOL_MAX = 1, EGTP_POOL_LAST = 2 } egtp_pool_kind;
+
+/* One prediction head (Section 3.2): x[d] -> relu(w1 x + b1)[d_h] -> w2 . + b2 [n_out]. */
+typedef struct {
+    int32_t d_h;              /* hidden width, > 0 */
+    int32_t n_out;            /* 1 = scalar length; K > 1 = K-bin head decoded with Eq. 6 (K <= 1024) */
+    egtp_dtype wdtype;        /* storage type of w1 and w2 */
+    const void *w1;           /* [d_h x d]     device */
+    const float *b1;          /* [d_h]         device, NULL = zeros */
+    const void *w2;           /* [n_out x d_h] device */
+    const float *b2;          /* [n_out]       device, NULL = zeros */
+    const float *bin_centers; /* [n_out]       device; required iff n_out > 1 (the c_i of Eq. 6) */
+} egtp_head;
+
+typedef struct {
+    int32_t d;          /* hidden size */
+    int32_t vocab;      /* vocabulary size V */
+    egtp_dtype dtype;   /* storage type of hidden states and w_lm */
+    const void *w_lm;   /* [vocab x d] device, must outlive the context */
+    float alpha;        /* pooling temperature, finite and > 0; 1.0f is Eq. 3 as printed */
+    egtp_head head_len; /* EGTP: predicted total length */
+    egtp_head head_rem; /* PLP: predicted remaining length; w1 == NULL means "use head_len" */
+} egtp_config;
+
+/* Validates the configuration, checks that the current device is gfx950 and records it.
+ * Makes no large allocation.  *out is set only on EGTP_OK. */
+egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out);
+egtp_status egtp_destroy(egtp_ctx *ctx);
+
+/* Bytes of workspace sufficient for any egtp_score / plp_step / egtp_pool_ablation call with
+ * at most max_tokens tokens and max_seqs sequences.  0 if an argument is invalid. */
+size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs);
+
+const char *egtp_status_string(egtp_status s);
+/* The hipError_t (as int) of the last failed HIP call made through this context, 0 if none. */
+int egtp_last_hip_error(const egtp_ctx *ctx);
+
+/* Ragged plumbing: offsets_dev[B+1] = exclusive prefix sum of lengths_dev[B] (int32; the caller
+ * guarantees the total fits), and, if seg_ids_dev != NULL, seg_ids_dev[t] = the sequence b with
+ * offsets[b] <= t < offsets[b+1] for t < T.  Integer work, exact. */
+egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_t B,
+                               int32_t *offsets_dev, int32_t *seg_ids_dev, int64_t T, void *stream);
+
+/* EGTP over one ragged batch (Eq. 2 -> Eq. 3 -> Eq. 4 -> head_len).
+ *   hidden        [T x d] cfg.dtype
+ *   offsets_dev   [B+1] device
+ *   offsets_host  optional host copy of the same offsets; when given it is checked here
+ *                 (EGTP_ERR_OFFSETS) before anything is launched
+ *   entropy_out   [T] fp32, optional (NULL: kept in the workspace only)
+ *   pooled_out    [B x d] fp32   \  together the PLP state of each sequence
+ *   lse_out       [B] fp32       /  lse_b = log sum_i exp(H_i/alpha)
+ *   pred_out      [B] fp32, predicted length
+ * No [T x vocab] logits tensor is written anywhere. */
+egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                       const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
+                       size_t workspace_bytes, float *entropy_out, float *pooled_out,
+                       float *lse_out, float *pred_out, void *stream);
+
+/* One PLP update (Eq. 8) for B live sequences: fold new tokens into each sequence's running
+ * state and predict the remaining length with head_rem.
+ *   hidden_new       [T_new x d] hidden states of the newly generated tokens
+ *   offsets_new_dev  [B+1] ragged offsets of the new tokens, or NULL = exactly one new token per
+ *                    sequence (then T_new must equal B)
+ *   offsets_new_host optional host mirror, checked like egtp_score's
+ *   slot_dev         optional [B]: sequence b lives in state row slot[b] (distinct, >= 0);
+ *                    NULL = row b
+ *   pooled_state     [S x d] fp32 in/out,  lse_state [S] fp32 in/out.  The empty state is
+ *                    (zeros, -inf); egtp_score's (pooled_out, lse_out) is the state after the prompt
+ *   entropy_out      [T_new] optional
+ *   rem_pred_out     [B] predicted remaining length
+ * With state (p, L) and new tokens (h_i, H_i):  L' = log(e^L + sum_i e^{H_i/alpha}),
+ * p' = p e^{L-L'} + sum_i h_i e^{H_i/alpha - L'}. */
+egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                     const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B,
+                     int64_t T_new, float *pooled_state, float *lse_state, void *workspace,
+                     size_t workspace_bytes, float *entropy_out, float *rem_pred_out, void *stream);
+
+/* Average / max / last-token pooling over the same ragged layout (Table 3's alternatives),
+ * followed by head_len.  pooled_out [B x d] fp32, pred_out [B] fp32 (optional).  An empty
+ * sequence pools to zeros. */
+egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                               const int32_t *offsets_host, int32_t B, int64_t T,
+                               egtp_pool_kind kind, void *workspace, size_t workspace_bytes,
+                               float *pooled_out, float *pred_out, void *stream);
+
+/* Measurement aid: when enabled, every egtp_score / plp_step call brackets its fused LM-head +
+ * entropy kernel (the Eq. 2 contraction, where nearly all of the work is) with a pair of HIP
+ * events on the call's stream.  The events are created here, not in the scoring calls; at most
+ * `capacity` (<= 1024) calls are recorded until the next read.  on == 0 disables and frees. */
+egtp_status egtp_profile_enable(egtp_ctx *ctx, int on, int capacity);
+/* After the stream has been synchronised: writes the elapsed milliseconds of each recorded
+ * kernel (oldest first) to ms_out[0..cap), returns how many were written and forgets them.
+ * Returns -1 on error. */
+int egtp_profile_read(egtp_ctx *ctx, float *ms_out_host, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGTP_H */

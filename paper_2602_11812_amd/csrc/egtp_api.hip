@@ -1,0 +1,487 @@
+// C ABI of the EGTP / PLP library: argument checks, workspace carving, launch sequencing.
+// Every arithmetic step runs in the kernels of this directory; nothing here computes.
+#include "../../include/egtp.h"
+
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "kernels.h"
+
+struct egtp_ctx {
+    egtp_config cfg;
+    int device;
+    int last_hip_error;
+    // optional event pairs around the fused entropy kernel (measurement aid)
+    hipEvent_t *prof_events;  // 2 * prof_cap events, or NULL
+    int prof_cap;
+    int prof_count;
+};
+
+namespace egtp {
+
+// ---- geometry of the fused entropy kernel ------------------------------------------------
+static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 4096;
+static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
+
+// EGTP_K1_VARIANT (0, 1, 2) picks the matrix-core kernel's K step / ring depth (tuning knob).
+static int k1_variant_from_env()
+{
+    const char *e = getenv("EGTP_K1_VARIANT");
+    return (e && e[0] >= '0' && e[0] <= '2' && e[1] == 0) ? e[0] - '0' : 0;
+}
+
+K1Plan k1_plan(int dtype, int64_t T, int d, int V)
+{
+    K1Plan p;
+    const bool mfma = dtype == DT_BF16 && k1_bf16_mfma_supported(d, V);
+    p.variant = mfma ? k1_variant_from_env() : -1;
+    p.tb_tokens = mfma ? BF16_TB : F32_TB;
+    p.tile_v = mfma ? BF16_TV : F32_TV;
+    const int target = mfma ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    p.ntb = (int)((T + p.tb_tokens - 1) / p.tb_tokens);
+    p.ntiles_v = (V + p.tile_v - 1) / p.tile_v;
+    int ns = p.ntb > 0 ? (target + p.ntb - 1) / p.ntb : 1;
+    if (ns < 1)
+        ns = 1;
+    if (ns > p.ntiles_v)
+        ns = p.ntiles_v;
+    p.tiles_per_split = (p.ntiles_v + ns - 1) / ns;
+    p.nsplit = (p.ntiles_v + p.tiles_per_split - 1) / p.tiles_per_split;
+    return p;
+}
+
+size_t k1_partial_floats(const K1Plan &p, int64_t T) { return (size_t)3 * (size_t)p.nsplit * (size_t)T; }
+
+size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V)
+{
+    // nsplit(T') * T' <= (target + ntb(T')) * tb_tokens for every T' <= T
+    const bool mfma = dtype == DT_BF16 && k1_bf16_mfma_supported(d, V);
+    const int64_t tbk = mfma ? BF16_TB : F32_TB;
+    const int64_t target = mfma ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const int64_t ntb = (T + tbk - 1) / tbk;
+    return (size_t)3 * (size_t)((target + ntb) * tbk);
+}
+
+}  // namespace egtp
+
+using namespace egtp;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Carves the caller's workspace; the same arithmetic gives egtp_workspace_bytes.
+struct Carver {
+    unsigned char *base;
+    size_t off;
+    explicit Carver(void *b) : base((unsigned char *)b), off(0) {}
+    template <typename Tp>
+    Tp *take(size_t count)
+    {
+        Tp *p = base ? (Tp *)(base + off) : nullptr;
+        off += up(count * sizeof(Tp));
+        return p;
+    }
+};
+
+struct Workspace {
+    float *entropy;      // [T]
+    float *k1_part;      // partial triples
+    int32_t *unit_start; // [B+1]
+    float *lse_new;      // [B]
+    float *state_scale;  // [B]
+    float *pool_part;    // [units_bound x d]
+    float *act;          // [B x d_h_max]
+    size_t bytes;
+};
+
+Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
+{
+    const egtp_config &c = ctx->cfg;
+    Carver cv(base);
+    Workspace w;
+    const int dh = c.head_len.d_h > c.head_rem.d_h ? c.head_len.d_h : c.head_rem.d_h;
+    w.entropy = cv.take<float>((size_t)T);
+    w.k1_part = cv.take<float>(k1_partial_floats_bound(c.dtype, T, c.d, c.vocab));
+    w.unit_start = cv.take<int32_t>((size_t)B + 1);
+    w.lse_new = cv.take<float>((size_t)B);
+    w.state_scale = cv.take<float>((size_t)B);
+    w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
+    w.act = cv.take<float>((size_t)B * (size_t)dh);
+    w.bytes = cv.off;
+    return w;
+}
+
+egtp_status check_head(const egtp_head &h)
+{
+    if (h.d_h <= 0 || h.n_out <= 0 || h.n_out > 1024)
+        return EGTP_ERR_SHAPE;
+    if (h.wdtype != EGTP_F32 && h.wdtype != EGTP_BF16)
+        return EGTP_ERR_DTYPE;
+    if (!h.w1 || !h.w2)
+        return EGTP_ERR_NULL;
+    if (h.n_out > 1 && !h.bin_centers)
+        return EGTP_ERR_NULL;
+    return EGTP_OK;
+}
+
+egtp_status check_offsets_host(const int32_t *o, int32_t B, int64_t T)
+{
+    if (o[0] != 0)
+        return EGTP_ERR_OFFSETS;
+    for (int32_t b = 0; b < B; ++b)
+        if (o[b + 1] < o[b])
+            return EGTP_ERR_OFFSETS;
+    if ((int64_t)o[B] != T)
+        return EGTP_ERR_OFFSETS;
+    return EGTP_OK;
+}
+
+egtp_status hip_fail(egtp_ctx *ctx, hipError_t e)
+{
+    ctx->last_hip_error = (int)e;
+    return EGTP_ERR_HIP;
+}
+
+#define EGTP_HIP(call)                \
+    do {                              \
+        hipError_t e_ = (call);       \
+        if (e_ != hipSuccess)         \
+            return hip_fail(ctx, e_); \
+    } while (0)
+
+// Eq. 2 for T tokens: fused partials, then the per-token merge into `entropy`.
+egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Workspace &w, float *entropy,
+                        hipStream_t st)
+{
+    const egtp_config &c = ctx->cfg;
+    const K1Plan p = k1_plan(c.dtype, T, c.d, c.vocab);
+    const bool timed = ctx->prof_events && ctx->prof_count < ctx->prof_cap;
+    if (timed)
+        EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count], st));
+    if (p.variant >= 0)
+        EGTP_HIP(k1_entropy_bf16(hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
+    else
+        EGTP_HIP(k1_entropy_simple(c.dtype, hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
+    if (timed) {
+        EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count + 1], st));
+        ++ctx->prof_count;
+    }
+    EGTP_HIP(k1_merge(w.k1_part, p.nsplit, T, entropy, st));
+    return EGTP_OK;
+}
+
+egtp_status run_head(egtp_ctx *ctx, const egtp_head &h, const float *x, const int32_t *slot, int32_t B,
+                     const Workspace &w, float *pred, hipStream_t st)
+{
+    HeadArgs a;
+    a.x = x;
+    a.slot = slot;
+    a.B = B;
+    a.d = ctx->cfg.d;
+    a.d_h = h.d_h;
+    a.n_out = h.n_out;
+    a.wdtype = h.wdtype;
+    a.w1 = h.w1;
+    a.b1 = h.b1;
+    a.w2 = h.w2;
+    a.b2 = h.b2;
+    a.bin_centers = h.bin_centers;
+    a.act = w.act;
+    a.pred = pred;
+    EGTP_HIP(head_forward(a, st));
+    return EGTP_OK;
+}
+
+egtp_status check_common(const egtp_ctx *ctx, int32_t B, int64_t T, const void *workspace, size_t ws_bytes)
+{
+    if (!ctx)
+        return EGTP_ERR_NULL;
+    if (B < 0 || T < 0 || T > 0x7fffffffLL)
+        return EGTP_ERR_SHAPE;
+    if (B == 0 && T != 0)
+        return EGTP_ERR_SHAPE;
+    if (B > 0) {
+        if (!workspace || ((uintptr_t)workspace % ALIGN) != 0)
+            return EGTP_ERR_WORKSPACE;
+        if (ws_bytes < egtp_workspace_bytes(ctx, T, B))
+            return EGTP_ERR_WORKSPACE;
+    }
+    return EGTP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *egtp_status_string(egtp_status s)
+{
+    switch (s) {
+    case EGTP_OK: return "ok";
+    case EGTP_ERR_NULL: return "a required pointer is NULL";
+    case EGTP_ERR_SHAPE: return "invalid or unsupported size";
+    case EGTP_ERR_OFFSETS: return "malformed offsets";
+    case EGTP_ERR_DTYPE: return "unknown storage type";
+    case EGTP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case EGTP_ERR_ARCH: return "current device is not gfx950";
+    case EGTP_ERR_HIP: return "HIP call failed";
+    case EGTP_ERR_ALPHA: return "temperature must be finite and > 0";
+    }
+    return "unknown status";
+}
+
+egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
+{
+    if (!cfg || !out)
+        return EGTP_ERR_NULL;
+    if (cfg->dtype != EGTP_F32 && cfg->dtype != EGTP_BF16)
+        return EGTP_ERR_DTYPE;
+    if (cfg->d <= 0 || cfg->vocab <= 0)
+        return EGTP_ERR_SHAPE;
+    if (cfg->d % (cfg->dtype == EGTP_BF16 ? 8 : 4) != 0)
+        return EGTP_ERR_SHAPE;  // rows must start on 16-byte boundaries
+    if ((int64_t)cfg->d * 2 * 256 > 0x7fffffffLL)
+        return EGTP_ERR_SHAPE;  // 32-bit byte offsets inside one 256-row tile
+    if (!cfg->w_lm)
+        return EGTP_ERR_NULL;
+    if (!(cfg->alpha > 0.0f) || !isfinite(cfg->alpha))
+        return EGTP_ERR_ALPHA;
+    egtp_status s = check_head(cfg->head_len);
+    if (s != EGTP_OK)
+        return s;
+    if (cfg->head_rem.w1) {
+        s = check_head(cfg->head_rem);
+        if (s != EGTP_OK)
+            return s;
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return EGTP_ERR_ARCH;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess || strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return EGTP_ERR_ARCH;
+    egtp_ctx *ctx = new (std::nothrow) egtp_ctx;
+    if (!ctx)
+        return EGTP_ERR_HIP;
+    ctx->cfg = *cfg;
+    if (!cfg->head_rem.w1)
+        ctx->cfg.head_rem = cfg->head_len;
+    ctx->device = dev;
+    ctx->last_hip_error = 0;
+    ctx->prof_events = nullptr;
+    ctx->prof_cap = 0;
+    ctx->prof_count = 0;
+    *out = ctx;
+    return EGTP_OK;
+}
+
+static void free_profile(egtp_ctx *ctx)
+{
+    if (ctx->prof_events) {
+        for (int i = 0; i < 2 * ctx->prof_cap; ++i)
+            if (ctx->prof_events[i])
+                (void)hipEventDestroy(ctx->prof_events[i]);
+        delete[] ctx->prof_events;
+    }
+    ctx->prof_events = nullptr;
+    ctx->prof_cap = 0;
+    ctx->prof_count = 0;
+}
+
+egtp_status egtp_destroy(egtp_ctx *ctx)
+{
+    if (ctx)
+        free_profile(ctx);
+    delete ctx;
+    return EGTP_OK;
+}
+
+egtp_status egtp_profile_enable(egtp_ctx *ctx, int on, int capacity)
+{
+    if (!ctx)
+        return EGTP_ERR_NULL;
+    free_profile(ctx);
+    if (!on)
+        return EGTP_OK;
+    if (capacity <= 0 || capacity > 1024)
+        return EGTP_ERR_SHAPE;
+    ctx->prof_events = new (std::nothrow) hipEvent_t[2 * capacity]();
+    if (!ctx->prof_events)
+        return EGTP_ERR_HIP;
+    ctx->prof_cap = capacity;
+    for (int i = 0; i < 2 * capacity; ++i) {
+        hipError_t e = hipEventCreate(&ctx->prof_events[i]);
+        if (e != hipSuccess) {
+            ctx->prof_events[i] = nullptr;
+            free_profile(ctx);
+            return hip_fail(ctx, e);
+        }
+    }
+    return EGTP_OK;
+}
+
+int egtp_profile_read(egtp_ctx *ctx, float *ms_out_host, int cap)
+{
+    if (!ctx || !ms_out_host || cap < 0)
+        return -1;
+    int n = ctx->prof_count < cap ? ctx->prof_count : cap;
+    for (int i = 0; i < n; ++i) {
+        hipError_t e = hipEventElapsedTime(&ms_out_host[i], ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]);
+        if (e != hipSuccess) {
+            ctx->last_hip_error = (int)e;
+            return -1;
+        }
+    }
+    ctx->prof_count = 0;
+    return n;
+}
+
+size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs)
+{
+    if (!ctx || max_tokens < 0 || max_seqs < 0 || max_tokens > 0x7fffffffLL)
+        return 0;
+    return carve(ctx, nullptr, max_tokens, max_seqs).bytes;
+}
+
+int egtp_last_hip_error(const egtp_ctx *ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_t B, int32_t *offsets_dev,
+                               int32_t *seg_ids_dev, int64_t T, void *stream)
+{
+    if (!ctx || !offsets_dev || (B > 0 && !lengths_dev))
+        return EGTP_ERR_NULL;
+    if (B < 0 || T < 0 || T > 0x7fffffffLL)
+        return EGTP_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    EGTP_HIP(scan_lengths(lengths_dev, B, offsets_dev, st));
+    if (seg_ids_dev && T > 0)
+        EGTP_HIP(segment_ids(offsets_dev, B, T, seg_ids_dev, st));
+    return EGTP_OK;
+}
+
+egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                       const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
+                       size_t workspace_bytes, float *entropy_out, float *pooled_out, float *lse_out,
+                       float *pred_out, void *stream)
+{
+    egtp_status s = check_common(ctx, B, T, workspace, workspace_bytes);
+    if (s != EGTP_OK)
+        return s;
+    if (B == 0)
+        return EGTP_OK;
+    if (!offsets_dev || !pooled_out || !lse_out || !pred_out || (T > 0 && !hidden))
+        return EGTP_ERR_NULL;
+    if (offsets_host && (s = check_offsets_host(offsets_host, B, T)) != EGTP_OK)
+        return s;
+
+    hipStream_t st = (hipStream_t)stream;
+    const egtp_config &c = ctx->cfg;
+    const Workspace w = carve(ctx, workspace, T, B);
+    float *entropy = entropy_out ? entropy_out : w.entropy;
+    if (T > 0 && (s = run_entropy(ctx, hidden, T, w, entropy, st)) != EGTP_OK)
+        return s;
+
+    PoolArgs a;
+    a.hidden = hidden;
+    a.dtype = c.dtype;
+    a.d = c.d;
+    a.entropy = entropy;
+    a.offsets = offsets_dev;
+    a.slot = nullptr;
+    a.B = B;
+    a.T = T;
+    a.inv_alpha = 1.0f / c.alpha;
+    a.state_lse = nullptr;
+    a.state_pooled = nullptr;
+    a.out_pooled = pooled_out;
+    a.out_lse = lse_out;
+    a.unit_start = w.unit_start;
+    a.lse_new = w.lse_new;
+    a.state_scale = w.state_scale;
+    a.partial = w.pool_part;
+    EGTP_HIP(pool_entropy_weighted(a, st));
+    return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
+}
+
+egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                     const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
+                     float *pooled_state, float *lse_state, void *workspace, size_t workspace_bytes,
+                     float *entropy_out, float *rem_pred_out, void *stream)
+{
+    egtp_status s = check_common(ctx, B, T_new, workspace, workspace_bytes);
+    if (s != EGTP_OK)
+        return s;
+    if (B == 0)
+        return EGTP_OK;
+    if (!pooled_state || !lse_state || !rem_pred_out || (T_new > 0 && !hidden_new))
+        return EGTP_ERR_NULL;
+    if (!offsets_new_dev) {
+        if (T_new != B)
+            return EGTP_ERR_SHAPE;
+        if (offsets_new_host)
+            return EGTP_ERR_OFFSETS;  // a host mirror of offsets that were not given
+    } else if (offsets_new_host && (s = check_offsets_host(offsets_new_host, B, T_new)) != EGTP_OK) {
+        return s;
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    const egtp_config &c = ctx->cfg;
+    const Workspace w = carve(ctx, workspace, T_new, B);
+    float *entropy = entropy_out ? entropy_out : w.entropy;
+    if (T_new > 0 && (s = run_entropy(ctx, hidden_new, T_new, w, entropy, st)) != EGTP_OK)
+        return s;
+
+    PoolArgs a;
+    a.hidden = hidden_new;
+    a.dtype = c.dtype;
+    a.d = c.d;
+    a.entropy = entropy;
+    a.offsets = offsets_new_dev;
+    a.slot = slot_dev;
+    a.B = B;
+    a.T = T_new;
+    a.inv_alpha = 1.0f / c.alpha;
+    a.state_lse = lse_state;
+    a.state_pooled = pooled_state;
+    a.out_pooled = pooled_state;
+    a.out_lse = lse_state;
+    a.unit_start = w.unit_start;
+    a.lse_new = w.lse_new;
+    a.state_scale = w.state_scale;
+    a.partial = w.pool_part;
+    EGTP_HIP(pool_entropy_weighted(a, st));
+    return run_head(ctx, c.head_rem, pooled_state, slot_dev, B, w, rem_pred_out, st);
+}
+
+egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                               const int32_t *offsets_host, int32_t B, int64_t T, egtp_pool_kind kind,
+                               void *workspace, size_t workspace_bytes, float *pooled_out, float *pred_out,
+                               void *stream)
+{
+    egtp_status s = check_common(ctx, B, T, workspace, workspace_bytes);
+    if (s != EGTP_OK)
+        return s;
+    if (kind != EGTP_POOL_AVERAGE && kind != EGTP_POOL_MAX && kind != EGTP_POOL_LAST)
+        return EGTP_ERR_SHAPE;
+    if (B == 0)
+        return EGTP_OK;
+    if (!offsets_dev || !pooled_out || (T > 0 && !hidden))
+        return EGTP_ERR_NULL;
+    if (offsets_host && (s = check_offsets_host(offsets_host, B, T)) != EGTP_OK)
+        return s;
+    hipStream_t st = (hipStream_t)stream;
+    const egtp_config &c = ctx->cfg;
+    EGTP_HIP(pool_plain(hidden, c.dtype, c.d, offsets_dev, B, (int)kind, pooled_out, st));
+    if (pred_out) {
+        const Workspace w = carve(ctx, workspace, T, B);
+        return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
+    }
+    return EGTP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,414 @@
+// Entropy-softmax weights and weighted pooling over ragged offsets (Eq. 3, Eq. 4), the
+// streaming PLP fold of Eq. 8, the ablation poolers of Table 3, and the ragged plumbing.
+//
+// Pooling is HBM-bound: every hidden state is read once more (16 bytes per lane, a wave
+// reads 1 KiB of one token row at a time).  A sequence is cut into units of at most
+// POOL_UNIT tokens so that long and short sequences load the chip evenly; each unit leaves a
+// partial weighted sum (already normalised with the sequence's final log-sum-exp), and a
+// finalize kernel adds a sequence's partials in unit order.  No atomics: bit-reproducible.
+#include "kernels.h"
+
+namespace egtp {
+namespace {
+
+constexpr float NEG_INF = -__builtin_inff();
+
+// ---- block reductions (256 threads), fixed tree => deterministic ---------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_xor(v, o);
+    return v;
+}
+__device__ float block_max(float v, float *sh)
+{
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+__device__ float block_sum(float v, float *sh)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+// ---- ragged plumbing ---------------------------------------------------------------------
+// offsets[0..B] = exclusive scan of f(lengths[b]); one workgroup walks the array in chunks
+// of 256 with a running carry.  UNITS: scan ceil(n_b / POOL_UNIT) of n_b = in[b+1]-in[b].
+template <bool UNITS>
+__global__ __launch_bounds__(256) void scan_kernel(const int32_t *__restrict__ in, int32_t B,
+                                                   int32_t *__restrict__ out)
+{
+    __shared__ int sh[256];
+    __shared__ int carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        carry = 0;
+        out[0] = 0;
+    }
+    __syncthreads();
+    for (int base = 0; base < B; base += 256) {
+        const int b = base + tid;
+        int v = 0;
+        if (b < B) {
+            if (UNITS) {
+                const int n = in[b + 1] - in[b];
+                v = (n + POOL_UNIT - 1) / POOL_UNIT;
+            } else {
+                v = in[b];
+            }
+        }
+        sh[tid] = v;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele scan
+            int add = tid >= o ? sh[tid - o] : 0;
+            __syncthreads();
+            sh[tid] += add;
+            __syncthreads();
+        }
+        if (b < B)
+            out[b + 1] = carry + sh[tid];
+        __syncthreads();
+        if (tid == 255)
+            carry += sh[255];
+        __syncthreads();
+    }
+}
+
+// largest b in [0, B) with arr[b] <= t, given arr[0] <= t < arr[B], arr non-decreasing
+__device__ __forceinline__ int find_segment(const int32_t *__restrict__ arr, int B, long t)
+{
+    int lo = 0, hi = B;  // invariant: arr[lo] <= t < arr[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (arr[mid] <= t)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void seg_ids_kernel(const int32_t *__restrict__ offsets, int32_t B,
+                                                      long T, int32_t *__restrict__ seg)
+{
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= T)
+        return;
+    seg[t] = (B > 0 && t < offsets[B]) ? find_segment(offsets, B, t) : -1;
+}
+
+// ---- Eq. 3: per-sequence log-sum-exp of H/alpha, joined with the old state's lse ---------
+__global__ __launch_bounds__(256) void pool_lse_kernel(const float *__restrict__ entropy,
+                                                       const int32_t *__restrict__ offsets,
+                                                       const int32_t *__restrict__ slot, float inv_alpha,
+                                                       const float *__restrict__ state_lse,
+                                                       float *__restrict__ lse_new,
+                                                       float *__restrict__ state_scale)
+{
+    __shared__ float sh[4];
+    const int b = blockIdx.x;
+    const int lo = offsets[b], hi = offsets[b + 1];
+    const int s = slot ? slot[b] : b;
+    const float L_old = state_lse ? state_lse[s] : NEG_INF;
+    float mx = NEG_INF;
+    for (int i = lo + threadIdx.x; i < hi; i += 256)
+        mx = fmaxf(mx, entropy[i] * inv_alpha);
+    mx = fmaxf(block_max(mx, sh), L_old);
+    float sum = 0.f;
+    if (mx > NEG_INF)
+        for (int i = lo + threadIdx.x; i < hi; i += 256)
+            sum += __expf(entropy[i] * inv_alpha - mx);
+    sum = block_sum(sum, sh);
+    if (threadIdx.x == 0) {
+        float L = NEG_INF, sc = 0.f;
+        if (mx > NEG_INF) {
+            const float old = L_old > NEG_INF ? __expf(L_old - mx) : 0.f;
+            L = mx + __logf(sum + old);
+            sc = L_old > NEG_INF ? __expf(L_old - L) : 0.f;
+        }
+        lse_new[b] = L;
+        state_scale[b] = sc;
+    }
+}
+
+// ---- Eq. 4: partial weighted sums per unit --------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void pool_partial_kernel(
+    const void *__restrict__ hidden, int d, const float *__restrict__ entropy,
+    const int32_t *__restrict__ offsets, int32_t B, float inv_alpha, const float *__restrict__ lse_new,
+    const int32_t *__restrict__ unit_start, float *__restrict__ partial)
+{
+    __shared__ float w[POOL_UNIT];
+    const int u = blockIdx.x;
+    if (u >= unit_start[B])
+        return;
+    const int b = find_segment(unit_start, B, u);
+    const long t0 = (long)offsets[b] + (long)(u - unit_start[b]) * POOL_UNIT;
+    const int n = (int)min((long)POOL_UNIT, (long)offsets[b + 1] - t0);
+    if (threadIdx.x < POOL_UNIT)
+        w[threadIdx.x] = threadIdx.x < n ? __expf(entropy[t0 + threadIdx.x] * inv_alpha - lse_new[b]) : 0.f;
+    __syncthreads();
+
+    constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte load
+    const int nchunk = d / VEC;
+    float *out = partial + (long)u * d;
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            acc[e] = 0.f;
+        const unsigned char *p = (const unsigned char *)hidden + (t0 * d + (long)c * VEC) * (BF16 ? 2 : 4);
+        const long stride = (long)d * (BF16 ? 2 : 4);
+        int i = 0;
+        for (; i + 4 <= n; i += 4) {
+            uint4 q[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                q[r] = *(const uint4 *)(p + (long)(i + r) * stride);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float wi = w[i + r];
+                if (BF16) {
+                    const unsigned v[4] = {q[r].x, q[r].y, q[r].z, q[r].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[2 * e] = fmaf(wi, __uint_as_float(v[e] << 16), acc[2 * e]);
+                        acc[2 * e + 1] = fmaf(wi, __uint_as_float(v[e] & 0xffff0000u), acc[2 * e + 1]);
+                    }
+                } else {
+                    acc[0] = fmaf(wi, __uint_as_float(q[r].x), acc[0]);
+                    acc[1] = fmaf(wi, __uint_as_float(q[r].y), acc[1]);
+                    acc[2] = fmaf(wi, __uint_as_float(q[r].z), acc[2]);
+                    acc[3] = fmaf(wi, __uint_as_float(q[r].w), acc[3]);
+                }
+            }
+        }
+        for (; i < n; ++i) {
+            const uint4 q = *(const uint4 *)(p + (long)i * stride);
+            const float wi = w[i];
+            if (BF16) {
+                const unsigned v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[2 * e] = fmaf(wi, __uint_as_float(v[e] << 16), acc[2 * e]);
+                    acc[2 * e + 1] = fmaf(wi, __uint_as_float(v[e] & 0xffff0000u), acc[2 * e + 1]);
+                }
+            } else {
+                acc[0] = fmaf(wi, __uint_as_float(q.x), acc[0]);
+                acc[1] = fmaf(wi, __uint_as_float(q.y), acc[1]);
+                acc[2] = fmaf(wi, __uint_as_float(q.z), acc[2]);
+                acc[3] = fmaf(wi, __uint_as_float(q.w), acc[3]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4)
+            *(float4 *)(out + (long)c * VEC + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+    }
+}
+
+// ---- sum a sequence's partials in unit order, add the rescaled old state ------------------
+__global__ __launch_bounds__(256) void pool_finalize_kernel(
+    const float *__restrict__ partial, const int32_t *__restrict__ unit_start,
+    const int32_t *__restrict__ slot, int d, const float *state_pooled,
+    const float *__restrict__ state_scale, const float *__restrict__ lse_new, float *out_pooled,
+    float *out_lse)
+{
+    const int b = blockIdx.x;
+    const int k = blockIdx.y * 256 + threadIdx.x;
+    const int s = slot ? slot[b] : b;
+    if (k < d) {
+        const int u0 = unit_start[b], u1 = unit_start[b + 1];
+        float sum = 0.f;
+        for (int u = u0; u < u1; ++u)
+            sum += partial[(long)u * d + k];
+        const float sc = state_scale[b];
+        if (state_pooled && sc != 0.f)
+            sum = fmaf(state_pooled[(long)s * d + k], sc, sum);
+        out_pooled[(long)s * d + k] = sum;
+    }
+    if (blockIdx.y == 0 && threadIdx.x == 0)
+        out_lse[s] = lse_new[b];
+}
+
+// ---- Eq. 8 fast path: exactly one new token per sequence ------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void plp_fold1_kernel(const void *__restrict__ hidden, int d,
+                                                        const float *__restrict__ entropy,
+                                                        const int32_t *__restrict__ slot, float inv_alpha,
+                                                        float *pooled_state, float *lse_state)
+{
+    const int b = blockIdx.x;
+    const int s = slot ? slot[b] : b;
+    const float L_old = lse_state[s];
+    const float a = entropy[b] * inv_alpha;
+    const float M = fmaxf(L_old, a);
+    const float old = L_old > NEG_INF ? __expf(L_old - M) : 0.f;
+    const float L = M + __logf(old + __expf(a - M));
+    const float sc = L_old > NEG_INF ? __expf(L_old - L) : 0.f;
+    const float wn = __expf(a - L);
+    __syncthreads();  // every thread has read the old lse before it is replaced
+    if (threadIdx.x == 0)
+        lse_state[s] = L;
+
+    constexpr int VEC = BF16 ? 8 : 4;
+    const int nchunk = d / VEC;
+    const unsigned char *hp = (const unsigned char *)hidden + (long)b * d * (BF16 ? 2 : 4);
+    float *pp = pooled_state + (long)s * d;
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        const uint4 q = *(const uint4 *)(hp + (long)c * 16);
+        float h[VEC];
+        if (BF16) {
+            const unsigned v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h[2 * e] = __uint_as_float(v[e] << 16);
+                h[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+            }
+        } else {
+            h[0] = __uint_as_float(q.x);
+            h[1] = __uint_as_float(q.y);
+            h[2] = __uint_as_float(q.z);
+            h[3] = __uint_as_float(q.w);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4) {
+            float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (sc != 0.f)
+                p = *(const float4 *)(pp + (long)c * VEC + e);
+            p.x = fmaf(p.x, sc, wn * h[e]);
+            p.y = fmaf(p.y, sc, wn * h[e + 1]);
+            p.z = fmaf(p.z, sc, wn * h[e + 2]);
+            p.w = fmaf(p.w, sc, wn * h[e + 3]);
+            *(float4 *)(pp + (long)c * VEC + e) = p;
+        }
+    }
+}
+
+// ---- Table 3 alternatives -----------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void pool_plain_kernel(const void *__restrict__ hidden, int d,
+                                                         const int32_t *__restrict__ offsets, int kind,
+                                                         float *__restrict__ out_pooled)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    const int b = blockIdx.x;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c * VEC >= d)
+        return;
+    const long lo = offsets[b], hi = offsets[b + 1];
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+        acc[e] = (kind == 1 && hi > lo) ? NEG_INF : 0.f;
+    const long first = kind == 2 ? (hi > lo ? hi - 1 : hi) : lo;
+    for (long t = first; t < hi; ++t) {
+        const uint4 q = *(const uint4 *)((const unsigned char *)hidden + (t * d + (long)c * VEC) * (BF16 ? 2 : 4));
+        float h[VEC];
+        if (BF16) {
+            const unsigned v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h[2 * e] = __uint_as_float(v[e] << 16);
+                h[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+            }
+        } else {
+            h[0] = __uint_as_float(q.x);
+            h[1] = __uint_as_float(q.y);
+            h[2] = __uint_as_float(q.z);
+            h[3] = __uint_as_float(q.w);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            acc[e] = kind == 1 ? fmaxf(acc[e], h[e]) : acc[e] + h[e];
+    }
+    if (kind == 0 && hi > lo) {
+        const float inv = 1.0f / (float)(hi - lo);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            acc[e] *= inv;
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+        out_pooled[(long)b * d + (long)c * VEC + e] = acc[e];
+}
+
+}  // namespace
+
+hipError_t scan_lengths(const int32_t *lengths, int32_t B, int32_t *offsets, hipStream_t st)
+{
+    hipLaunchKernelGGL(scan_kernel<false>, dim3(1), dim3(256), 0, st, lengths, B, offsets);
+    return hipGetLastError();
+}
+
+hipError_t segment_ids(const int32_t *offsets, int32_t B, int64_t T, int32_t *seg, hipStream_t st)
+{
+    if (T <= 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(seg_ids_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, offsets, B,
+                       (long)T, seg);
+    return hipGetLastError();
+}
+
+hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
+{
+    if (a.B <= 0)
+        return hipSuccess;
+    const bool bf16 = a.dtype == DT_BF16;
+    if (a.offsets == nullptr) {  // one new token per sequence, folded in place
+        if (bf16)
+            hipLaunchKernelGGL(plp_fold1_kernel<true>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d,
+                               a.entropy, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
+        else
+            hipLaunchKernelGGL(plp_fold1_kernel<false>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d,
+                               a.entropy, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(256), 0, st, a.offsets, a.B, a.unit_start);
+    hipLaunchKernelGGL(pool_lse_kernel, dim3(a.B), dim3(256), 0, st, a.entropy, a.offsets, a.slot,
+                       a.inv_alpha, a.state_lse, a.lse_new, a.state_scale);
+    const long units = pool_units_bound(a.T, a.B);
+    if (units > 0x7fffffffL)
+        return hipErrorInvalidValue;
+    if (bf16)
+        hipLaunchKernelGGL(pool_partial_kernel<true>, dim3((unsigned)units), dim3(256), 0, st, a.hidden,
+                           a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
+    else
+        hipLaunchKernelGGL(pool_partial_kernel<false>, dim3((unsigned)units), dim3(256), 0, st, a.hidden,
+                           a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
+    hipLaunchKernelGGL(pool_finalize_kernel, dim3(a.B, (a.d + 255) / 256), dim3(256), 0, st, a.partial,
+                       a.unit_start, a.slot, a.d, a.state_pooled, a.state_scale, a.lse_new, a.out_pooled,
+                       a.out_lse);
+    return hipGetLastError();
+}
+
+hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B, int kind,
+                      float *out_pooled, hipStream_t st)
+{
+    if (B <= 0)
+        return hipSuccess;
+    const int vec = dtype == DT_BF16 ? 8 : 4;
+    const dim3 grid(B, (d / vec + 255) / 256);
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(pool_plain_kernel<true>, grid, dim3(256), 0, st, hidden, d, offsets, kind, out_pooled);
+    else
+        hipLaunchKernelGGL(pool_plain_kernel<false>, grid, dim3(256), 0, st, hidden, d, offsets, kind, out_pooled);
+    return hipGetLastError();
+}
+
+}  // namespace egtp

@@ -1,0 +1,94 @@
+// Internal launcher interface between the C-ABI layer and the gfx950 kernels.
+// Nothing here is exported; all pointers are device pointers unless stated otherwise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace egtp {
+
+// Storage types of hidden states / weights (values match the public enum).
+enum : int { DT_F32 = 0, DT_BF16 = 1 };
+
+// Geometry of the fused LM-head + entropy kernel: tokens are cut into blocks of `tb_tokens`,
+// the vocabulary into `nsplit` ranges of `tiles_per_split` tiles of `tile_v` rows; each
+// (token block, vocabulary range) pair is one workgroup and leaves one partial (m, S, U)
+// triple per token.
+struct K1Plan {
+    int tb_tokens;        // tokens per block
+    int tile_v;           // vocabulary rows per tile
+    int ntb;              // token blocks
+    int ntiles_v;         // vocabulary tiles in total
+    int nsplit;           // vocabulary ranges
+    int tiles_per_split;  // tiles per range (last range may hold fewer)
+    int variant;          // kernel flavour: 0 = matrix-core kernel, K step 64, 2 LDS stages; 1 = K step 32,
+                          // 4 stages; 2 = K step 32, 3 stages; -1 = plain FMA kernel
+};
+
+// true when the matrix-core kernel can take this shape (else the plain FMA kernel runs)
+bool k1_bf16_mfma_supported(int d, int V);
+
+K1Plan k1_plan(int dtype, int64_t T, int d, int V);
+// floats needed for the partial triples of a plan (3 * nsplit * T)
+size_t k1_partial_floats(const K1Plan &p, int64_t T);
+// upper bound of k1_partial_floats over every T' <= T
+size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
+
+// Eq. 2, fused: partial (max, sum e^{z-m}, sum e^{z-m}(z-m) log2 e) per token and vocabulary range.
+hipError_t k1_entropy_bf16(const void *hidden, const void *w_lm, int64_t T, int d, int V,
+                           const K1Plan &p, float *part, hipStream_t st);
+// plain fp32-FMA kernel for fp32 inputs and for bf16 shapes the matrix-core kernel does not take
+hipError_t k1_entropy_simple(int dtype, const void *hidden, const void *w_lm, int64_t T, int d, int V,
+                             const K1Plan &p, float *part, hipStream_t st);
+// merges the nsplit partial triples of each token in a fixed order; entropy[t] = ln S - U/S
+hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st);
+
+// Ragged plumbing.
+hipError_t scan_lengths(const int32_t *lengths, int32_t B, int32_t *offsets, hipStream_t st);
+hipError_t segment_ids(const int32_t *offsets, int32_t B, int64_t T, int32_t *seg, hipStream_t st);
+
+// Eq. 3 / Eq. 4 / Eq. 8 over ragged offsets.  A sequence is cut into units of at most
+// POOL_UNIT tokens; unit_start[B+1] is the exclusive scan of units per sequence.
+constexpr int POOL_UNIT = 64;
+inline int64_t pool_units_bound(int64_t T, int32_t B) { return (T + POOL_UNIT - 1) / POOL_UNIT + B; }
+
+struct PoolArgs {
+    const void *hidden;       // [T x d]
+    int dtype;
+    int d;
+    const float *entropy;     // [T]
+    const int32_t *offsets;   // [B+1], or NULL = one token per sequence
+    const int32_t *slot;      // [B] or NULL
+    int32_t B;
+    int64_t T;
+    float inv_alpha;
+    const float *state_lse;   // [S] old state or NULL (= empty state)
+    const float *state_pooled;// [S x d] old state or NULL
+    float *out_pooled;        // [S x d] (may alias state_pooled)
+    float *out_lse;           // [S]     (may alias state_lse)
+    // workspace
+    int32_t *unit_start;      // [B+1]
+    float *lse_new;           // [B]
+    float *state_scale;       // [B]
+    float *partial;           // [units_bound x d]
+};
+hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st);
+
+// Table 3 alternatives: kind 0 average, 1 max, 2 last token.
+hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B,
+                      int kind, float *out_pooled, hipStream_t st);
+
+// Prediction head.
+struct HeadArgs {
+    const float *x;           // [S x d] pooled vectors
+    const int32_t *slot;      // [B] row of x per sequence, or NULL = identity
+    int32_t B;
+    int d, d_h, n_out, wdtype;
+    const void *w1; const float *b1;
+    const void *w2; const float *b2;
+    const float *bin_centers; // [n_out] when n_out > 1
+    float *act;               // workspace [B x d_h]
+    float *pred;              // [B]
+};
+hipError_t head_forward(const HeadArgs &a, hipStream_t st);
+
+}  // namespace egtp

@@ -1,0 +1,338 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
+seeded inputs.  Integer work is compared bit for bit; floating point to the stated bars."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import (TOL_ENTROPY_ABS, TOL_LSE_ABS, TOL_POOLED_REL_L2, assert_egtp_close, assert_pred_close, rel_l2)
+from paper_2602_11812_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2602_11812_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load_library()
+    return binding
+
+
+def _np(d):
+    return {k: v.cpu().numpy() for k, v in d.items()}
+
+
+def _scorer(gpu, w, alpha=1.0, b1=None, b2=None, w2=None, centers=None, head_rem=None):
+    td = gpu.to_device
+    head = gpu.make_head(td(w.w1), td(w.w2 if w2 is None else w2),
+                         None if b1 is None else td(b1), None if b2 is None else td(b2),
+                         None if centers is None else td(centers))
+    return gpu.Scorer(td(w.w_lm), head, head_rem, alpha)
+
+
+def _offsets_on_gpu(gpu, sc, lengths, want_seg=False):
+    import torch
+    T = int(np.sum(lengths))
+    return sc.build_offsets(torch.from_numpy(np.asarray(lengths, dtype=np.int32)).cuda(), T, want_seg)
+
+
+def _run(gpu, w, lengths=None, **kw):
+    sc = _scorer(gpu, w, **kw)
+    lengths = w.lengths if lengths is None else lengths
+    off = _offsets_on_gpu(gpu, sc, lengths)
+    out = _np(sc.score(gpu.to_device(w.hidden), off))
+    out["offsets"] = off.cpu().numpy()
+    return out
+
+
+# ----------------------------------------------------------------------------- fp32 tiny workload
+def test_tiny_fp32_end_to_end(gpu):
+    w = wl.make(wl.SPECS["tiny"])
+    got = _run(gpu, w)
+    off = oracle.offsets_from_lengths(w.lengths)
+    assert np.array_equal(got["offsets"], off) and got["offsets"].dtype == np.int32
+    assert got["offsets"].tolist() == [0, 17, 81, 181, 309]
+    want = oracle.egtp(w.hidden, off, w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+def test_offsets_and_segment_ids_bit_exact(gpu):
+    w = wl.make(wl.SPECS["tiny"])
+    sc = _scorer(gpu, w)
+    rng = np.random.default_rng(0)
+    for lens in ([17, 64, 100, 128], [0, 3, 0, 0, 2, 1, 0], [5], [0], rng.integers(0, 40, size=700).tolist(),
+                 rng.integers(0, 3, size=2000).tolist()):
+        T = int(np.sum(lens))
+        off, seg = _offsets_on_gpu(gpu, sc, lens, want_seg=True)
+        want_off = oracle.offsets_from_lengths(lens)
+        assert np.array_equal(off.cpu().numpy(), want_off)
+        assert np.array_equal(seg.cpu().numpy(), oracle.seg_ids(want_off, T))
+
+
+# ----------------------------------------------------------------------------- bf16 matrix-core kernel
+def _small_bf16(seed=1, B=6, d=512, V=2500, d_h=96, lengths=None, lo=16, hi=400):
+    spec = wl.scaled(wl.SPECS["mid"], seed=seed, B=B, d=d, V=V, d_h=d_h, len_lo=lo, len_hi=hi,
+                     len_mu=5.0, len_sigma=0.8, lengths=lengths)
+    return wl.make(spec)
+
+
+@pytest.mark.parametrize("variant", ["0", "1", "2"])
+def test_bf16_mfma_several_tiles_and_ragged_tails(gpu, variant, monkeypatch):
+    # V = 2500 -> 10 vocabulary tiles, the last one ragged; T spans several 256-token blocks
+    # with a ragged last block; d = 512 -> 8 (or 16) K steps through the LDS ring
+    monkeypatch.setenv("EGTP_K1_VARIANT", variant)
+    w = _small_bf16()
+    assert w.T > 600 and w.T % 256 != 0
+    got = _run(gpu, w)
+    off = oracle.offsets_from_lengths(w.lengths)
+    want = oracle.egtp(w.hidden, off, w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+@pytest.mark.parametrize("T,V,d", [(1, 256, 64), (255, 257, 64), (256, 511, 128), (257, 512, 192), (513, 1000, 320)])
+def test_bf16_mfma_edge_sizes(gpu, T, V, d):
+    w = _small_bf16(seed=7, B=1, d=d, V=V, d_h=8, lengths=(T,))
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, [0, T], w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+def test_bf16_plain_kernel_for_unaligned_shapes(gpu):
+    # d not a multiple of 64 and a vocabulary below one tile take the plain FMA kernel
+    for d, V in ((72, 100), (128, 200), (40, 3000)):
+        w = _small_bf16(seed=3, B=3, d=d, V=V, d_h=16, lengths=(5, 70, 1))
+        got = _run(gpu, w)
+        want = oracle.egtp(w.hidden, [0, 5, 75, 76], w.w_lm, oracle.Head(w.w1, w.w2))
+        assert_egtp_close(got, want)
+
+
+def test_closed_forms_on_gpu(gpu):
+    import torch
+    # zero LM head: every entropy is ln V, pooling is the plain mean
+    w = _small_bf16(seed=5, B=3, d=128, V=1187, d_h=8, lengths=(10, 1, 300))
+    w.w_lm[:] = 0
+    got = _run(gpu, w)
+    assert np.abs(got["entropy"] - math.log(1187)).max() < 1e-5
+    hf = wl.bf16_bits_to_f32(w.hidden).astype(np.float64)
+    off = [0, 10, 11, 311]
+    for b in range(3):
+        assert rel_l2(got["pooled"][b], hf[off[b]:off[b + 1]].mean(axis=0)) < 1e-5
+    assert np.allclose(got["lse"], math.log(1187) + np.log([10, 1, 300]), atol=1e-4)
+    # one vocabulary row aligned with the hidden state dominates: entropy -> closed form
+    V, d = 1000, 64
+    W = np.zeros((V, d), dtype=np.float32)
+    W[123, 0] = 4.0
+    h = np.zeros((3, d), dtype=np.float32)
+    h[:, 0] = [1.0, 3.0, 10.0]          # logit c = 4, 12, 40 on one row, 0 elsewhere
+    w2 = wl.Workload(w.spec, np.array([3], np.int32), wl.to_bf16_bits(h), wl.to_bf16_bits(W),
+                     wl.to_bf16_bits(np.ones((4, d), np.float32)), wl.to_bf16_bits(np.ones((1, 4), np.float32)))
+    got = _run(gpu, w2)
+    for i, c in enumerate((4.0, 12.0, 40.0)):
+        Z = math.exp(c) + V - 1
+        assert abs(got["entropy"][i] - (math.log(Z) - c * math.exp(c) / Z)) < 1e-4
+
+
+def test_empty_and_single_token_sequences(gpu):
+    lens = (0, 1, 0, 300, 1, 0)
+    w = _small_bf16(seed=11, B=6, d=256, V=600, d_h=32, lengths=lens)
+    b1 = np.random.default_rng(0).normal(size=32).astype(np.float32)
+    b2 = np.array([0.75], dtype=np.float32)
+    got = _run(gpu, w, b1=b1, b2=b2)
+    off = oracle.offsets_from_lengths(lens)
+    want = oracle.egtp(w.hidden, off, w.w_lm, oracle.Head(w.w1, w.w2, b1, b2))
+    assert_egtp_close(got, want)
+    hf = wl.bf16_bits_to_f32(w.hidden)
+    for b, n in enumerate(lens):
+        if n == 0:
+            assert not got["pooled"][b].any() and got["lse"][b] == -np.inf
+        if n == 1:
+            assert np.array_equal(got["pooled"][b], hf[off[b]])     # weight is exactly 1
+
+
+@pytest.mark.parametrize("alpha", [0.5, 4.0])
+def test_temperature(gpu, alpha):
+    w = _small_bf16(seed=13, B=4, d=128, V=700, d_h=16)
+    got = _run(gpu, w, alpha=alpha)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2), alpha)
+    assert_egtp_close(got, want)
+
+
+def test_k_bin_head_expected_value(gpu):
+    K = 20
+    w = _small_bf16(seed=17, B=5, d=128, V=500, d_h=48)
+    rng = np.random.default_rng(1)
+    w2 = wl.to_bf16_bits(rng.normal(0, 1.0, size=(K, 48)).astype(np.float32))
+    b2 = rng.normal(size=K).astype(np.float32)
+    centers = np.linspace(16.0, 4096.0, K).astype(np.float32)
+    got = _run(gpu, w, w2=w2, b2=b2, centers=centers)
+    head = oracle.Head(w.w1, w2, None, b2, centers.astype(np.float64))
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, head)
+    assert_egtp_close(got, want)
+
+
+def test_deterministic_and_batch_invariant(gpu):
+    w = _small_bf16(seed=19, B=5, d=256, V=1500, d_h=32)
+    sc = _scorer(gpu, w)
+    off = _offsets_on_gpu(gpu, sc, w.lengths)
+    hd = gpu.to_device(w.hidden)
+    a = _np(sc.score(hd, off))
+    b = _np(sc.score(hd, off))
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k                       # run-to-run bit identical
+    offs = oracle.offsets_from_lengths(w.lengths)
+    for s in (0, 3):                                               # a sequence scored alone
+        import torch
+        one = _np(sc.score(hd[offs[s]:offs[s + 1]].contiguous(), torch.tensor([0, w.lengths[s]], dtype=torch.int32).cuda()))
+        assert np.abs(one["entropy"] - a["entropy"][offs[s]:offs[s + 1]]).max() < 1e-5
+        assert rel_l2(one["pooled"][0], a["pooled"][s]) < 1e-5
+
+
+def test_vocabulary_permutation_invariance(gpu):
+    w = _small_bf16(seed=23, B=2, d=128, V=1300, d_h=8)
+    a = _run(gpu, w)
+    perm = np.random.default_rng(0).permutation(1300)
+    w.w_lm = np.ascontiguousarray(w.w_lm[perm])
+    b = _run(gpu, w)
+    assert np.abs(a["entropy"] - b["entropy"]).max() < 2e-5
+
+
+def test_ablation_poolers(gpu):
+    lens = (4, 0, 33, 1)
+    w = _small_bf16(seed=29, B=4, d=128, V=300, d_h=16, lengths=lens)
+    sc = _scorer(gpu, w)
+    off = _offsets_on_gpu(gpu, sc, lens)
+    ooff = oracle.offsets_from_lengths(lens)
+    head = oracle.Head(w.w1, w.w2)
+    for kind in (gpu.EGTP_POOL_AVERAGE, gpu.EGTP_POOL_MAX, gpu.EGTP_POOL_LAST):
+        pooled, pred = sc.pool_ablation(gpu.to_device(w.hidden), off, kind)
+        want = oracle.pool_ablation(w.hidden, ooff, kind)
+        got = pooled.cpu().numpy()
+        assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max())
+        assert_pred_close(pred.cpu().numpy(), oracle.predict(want, head))
+    # fp32 storage too
+    wt = wl.make(wl.SPECS["tiny"])
+    sc = _scorer(gpu, wt)
+    off = _offsets_on_gpu(gpu, sc, wt.lengths)
+    pooled, _ = sc.pool_ablation(gpu.to_device(wt.hidden), off, gpu.EGTP_POOL_AVERAGE)
+    want = oracle.pool_ablation(wt.hidden, oracle.offsets_from_lengths(wt.lengths), oracle.POOL_AVERAGE)
+    assert np.abs(pooled.cpu().numpy() - want).max() < 1e-5
+
+
+# ----------------------------------------------------------------------------- PLP (Eq. 8)
+def _plp_setup(gpu, seed=31, B=5, d=256, V=900, d_h=24, steps=4):
+    w = _small_bf16(seed=seed, B=B, d=d, V=V, d_h=d_h, lo=1, hi=60)
+    rng = np.random.default_rng(seed + 1)
+    rem_w1 = wl.to_bf16_bits(rng.normal(0, d ** -0.5, size=(d_h, d)).astype(np.float32))
+    rem_w2 = wl.to_bf16_bits(rng.normal(0, d_h ** -0.5, size=(1, d_h)).astype(np.float32))
+    gen = [wl.decode_hidden(w.spec, t + 1) for t in range(steps)]
+    td = gpu.to_device
+    sc = _scorer(gpu, w, head_rem=gpu.make_head(td(rem_w1), td(rem_w2)))
+    return w, sc, gen, oracle.Head(rem_w1, rem_w2)
+
+
+def test_plp_steps_match_egtp_on_concatenation(gpu):
+    import torch
+    w, sc, gen, head_rem = _plp_setup(gpu)
+    off = _offsets_on_gpu(gpu, sc, w.lengths)
+    out = sc.score(gpu.to_device(w.hidden), off)
+    pooled, lse = out["pooled"].clone(), out["lse"].clone()
+    want = oracle.plp(w.hidden, oracle.offsets_from_lengths(w.lengths), gen, w.w_lm, head_rem)
+    for t, g in enumerate(gen):
+        ent = torch.empty(w.spec.B, dtype=torch.float32, device="cuda")
+        pred = sc.step(gpu.to_device(g), pooled, lse, entropy_out=ent)
+        r = want[t]
+        new_tok = oracle.offsets_from_lengths(np.asarray(w.lengths) + t + 1)[1:] - 1   # last token of each sequence
+        assert np.abs(ent.cpu().numpy() - r.entropy[new_tok]).max() <= TOL_ENTROPY_ABS
+        for b in range(w.spec.B):
+            assert rel_l2(pooled[b].cpu().numpy(), r.pooled[b]) <= TOL_POOLED_REL_L2
+        assert np.abs(lse.cpu().numpy() - r.lse).max() <= TOL_LSE_ABS
+        assert_pred_close(pred.cpu().numpy(), r.pred)
+
+
+def test_plp_from_empty_state_with_slots_and_checkpoint(gpu):
+    import torch
+    w, sc, gen, head_rem = _plp_setup(gpu, seed=37, steps=6)
+    B, d = w.spec.B, w.spec.d
+    S = B + 3
+    slot = np.array([6, 0, 3, 7, 2], dtype=np.int32)
+    slot_dev = torch.from_numpy(slot).cuda()
+    pooled = torch.zeros(S, d, dtype=torch.float32, device="cuda")
+    lse = torch.full((S,), -math.inf, dtype=torch.float32, device="cuda")
+    empty = np.zeros((0, d), dtype=np.uint16)
+    want = oracle.plp(empty, np.zeros(B + 1, np.int32), gen, w.w_lm, head_rem)
+    snap = None
+    for t, g in enumerate(gen):
+        pred = sc.step(gpu.to_device(g), pooled, lse, slot_dev=slot_dev)
+        if t == 2:
+            snap = (pooled.clone(), lse.clone())
+        for b in range(B):
+            assert rel_l2(pooled[slot[b]].cpu().numpy(), want[t].pooled[b]) <= TOL_POOLED_REL_L2
+        assert_pred_close(pred.cpu().numpy(), want[t].pred)
+    unused = [s for s in range(S) if s not in slot]
+    assert not pooled[unused].any().item() and torch.isinf(lse[unused]).all().item()
+    # resume from the snapshot: bit-identical continuation
+    p2, l2 = snap
+    for g in gen[3:]:
+        sc.step(gpu.to_device(g), p2, l2, slot_dev=slot_dev)
+    assert torch.equal(p2, pooled) and torch.equal(l2, lse)
+
+
+def test_plp_ragged_chunk_fold_equals_single_folds(gpu):
+    import torch
+    w, sc, gen, head_rem = _plp_setup(gpu, seed=41, steps=5)
+    B = w.spec.B
+    off = _offsets_on_gpu(gpu, sc, w.lengths)
+    out = sc.score(gpu.to_device(w.hidden), off)
+    # ragged fold: sequence b receives chunk_len[b] of the generated tokens in one call
+    chunk_len = np.array([5, 0, 3, 1, 5], dtype=np.int32)
+    rows = [gen[s][b] for b in range(B) for s in range(chunk_len[b])]
+    chunk = np.stack(rows)
+    coff = oracle.offsets_from_lengths(chunk_len)
+    pooled, lse = out["pooled"].clone(), out["lse"].clone()
+    pred = sc.step(gpu.to_device(chunk), pooled, lse, offsets_new_dev=torch.from_numpy(coff).cuda(),
+                   offsets_new_host=coff)
+    # oracle: EGTP over prompt + that sequence's chunk
+    poff = oracle.offsets_from_lengths(w.lengths)
+    cat, lens = [], []
+    for b in range(B):
+        cat.append(w.hidden[poff[b]:poff[b + 1]])
+        cat.append(chunk[coff[b]:coff[b + 1]])
+        lens.append(int(w.lengths[b] + chunk_len[b]))
+    want = oracle.egtp(np.concatenate(cat), oracle.offsets_from_lengths(lens), w.w_lm, head_rem)
+    for b in range(B):
+        assert rel_l2(pooled[b].cpu().numpy(), want.pooled[b]) <= TOL_POOLED_REL_L2
+    assert np.abs(lse.cpu().numpy() - want.lse).max() <= TOL_LSE_ABS
+    assert_pred_close(pred.cpu().numpy(), want.pred)
+
+
+# ----------------------------------------------------------------------------- error paths (host side)
+def test_error_codes_before_any_launch(gpu):
+    import torch
+    w = _small_bf16(seed=43, B=2, d=64, V=300, d_h=8, lengths=(3, 4))
+    sc = _scorer(gpu, w)
+    hd = gpu.to_device(w.hidden)
+    off = torch.tensor([0, 3, 7], dtype=torch.int32).cuda()
+    outs = [torch.empty(7, device="cuda"), torch.empty(2, 64, device="cuda"), torch.empty(2, device="cuda"),
+            torch.empty(2, device="cuda")]
+    ws = sc.workspace(7, 2)
+
+    def status(fn):
+        with pytest.raises(gpu.EgtpError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, [0, 4, 3], 2, 7, ws, *outs)) == 3      # decreasing
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, [1, 3, 7], 2, 7, ws, *outs)) == 3      # offsets[0] != 0
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, [0, 3, 6], 2, 7, ws, *outs)) == 3      # offsets[B] != T
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, None, 2, 7, ws[:256], *outs)) == 5     # too small
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, None, 2, 7, ws[16:], *outs)) == 5      # misaligned
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, off, None, -1, 7, ws, *outs)) == 2
+    assert status(lambda: gpu.egtp_score(sc.ctx, hd, None, None, 2, 7, ws, *outs)) == 1
+    assert status(lambda: gpu.plp_step(sc.ctx, hd, None, None, None, 2, 7, outs[1], outs[2], ws, None, outs[3])) == 2
+    gpu.egtp_score(sc.ctx, hd, off, [0, 3, 7], 0, 0, None, None, None, None, None)               # B == 0: nothing to do
+    gpu.egtp_score(sc.ctx, hd, off, [0, 3, 7], 2, 7, ws, *outs)                                  # and the good call works
+    torch.cuda.synchronize()
