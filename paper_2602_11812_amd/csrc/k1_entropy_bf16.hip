@@ -68,6 +68,8 @@ __device__ __forceinline__ void fold_tile(const f32x16 &a, Stats &st, int row0, 
 #pragma unroll
     for (int i = 1; i < 16; ++i)
         mx = fmaxf(mx, z[i]);
+    if (MASK && !(mx > NEG_BIG))
+        return;  // every row of this lane is masked: nothing to add (and no reference maximum yet)
     if (mx > st.m) {  // new running maximum: rescale what has been summed so far
         float dl = (st.m - mx) * LOG2E;
         float sc = fast_exp2(dl);

@@ -130,6 +130,8 @@ __global__ __launch_bounds__(256) void k1_entropy_simple_kernel(
             for (int i = 0; i < 4; ++i)
                 z[i] = (v0 + tx * 4 + i < V) ? acc[i][j] : NEG_BIG;
             const float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+            if (!(mx > NEG_BIG))
+                continue;  // all four rows are past the vocabulary: nothing to add
             if (mx > st[j].m) {
                 const float dl = (st[j].m - mx) * LOG2E;
                 const float sc = __builtin_amdgcn_exp2f(dl);
