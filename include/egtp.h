@@ -90,6 +90,18 @@ typedef struct {
 egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out);
 egtp_status egtp_destroy(egtp_ctx *ctx);
 
+/* The bf16 matrix-core kernel reads W_lm from a packed copy (tiles of 256 rows x 32 hidden
+ * elements, contiguous per tile and K step).  egtp_pack_w_lm builds that copy once into
+ * packed_dev (device memory of at least egtp_packed_w_lm_bytes(), 256-byte aligned, borrowed:
+ * it must stay valid and unmodified while the context uses it; enqueued on `stream`, and later
+ * scoring calls must be ordered after it).  Without it every scoring call re-packs W_lm into
+ * its workspace first -- fine for large prefill batches, wasteful for decode steps.  Calling it
+ * again re-packs (after w_lm changed); packed_dev == NULL forgets the copy.  Changing between
+ * "packed" and "not packed" changes egtp_workspace_bytes().  fp32 contexts: bytes = 0,
+ * packing is EGTP_ERR_DTYPE. */
+size_t egtp_packed_w_lm_bytes(const egtp_ctx *ctx);
+egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *stream);
+
 /* Bytes of workspace sufficient for any egtp_score / plp_step / egtp_pool_ablation call with
  * at most max_tokens tokens and max_seqs sequences.  0 if an argument is invalid. */
 size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs);

@@ -23,7 +23,7 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
-           "egtp_profile_enable", "egtp_profile_read")
+           "egtp_profile_enable", "egtp_profile_read", "egtp_packed_w_lm_bytes", "egtp_pack_w_lm")
 
 
 class egtp_head(Structure):
@@ -74,6 +74,10 @@ def load_library() -> ctypes.CDLL:
     lib.plp_step.restype = c_int
     lib.egtp_pool_ablation.argtypes = [vp, vp, vp, vp, i32, i64, c_int, vp, c_size_t, vp, vp, vp]
     lib.egtp_pool_ablation.restype = c_int
+    lib.egtp_packed_w_lm_bytes.argtypes = [vp]
+    lib.egtp_packed_w_lm_bytes.restype = c_size_t
+    lib.egtp_pack_w_lm.argtypes = [vp, vp, c_size_t, vp]
+    lib.egtp_pack_w_lm.restype = c_int
     lib.egtp_profile_enable.argtypes = [vp, c_int, c_int]
     lib.egtp_profile_enable.restype = c_int
     lib.egtp_profile_read.argtypes = [vp, vp, c_int]
@@ -153,6 +157,17 @@ def egtp_workspace_bytes(ctx, max_tokens: int, max_seqs: int) -> int:
     return int(load_library().egtp_workspace_bytes(ctx, int(max_tokens), int(max_seqs)))
 
 
+def egtp_packed_w_lm_bytes(ctx) -> int:
+    return int(load_library().egtp_packed_w_lm_bytes(ctx))
+
+
+def egtp_pack_w_lm(ctx, packed_dev, stream=None) -> None:
+    nbytes = packed_dev.numel() * packed_dev.element_size() if packed_dev is not None else 0
+    st = load_library().egtp_pack_w_lm(ctx, _dev(packed_dev), nbytes, _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_pack_w_lm")
+
+
 def egtp_last_hip_error(ctx) -> int:
     return int(load_library().egtp_last_hip_error(ctx))
 
@@ -217,7 +232,7 @@ class Scorer:
     """Owns a context plus torch-allocated outputs and workspace.  No arithmetic here."""
 
     def __init__(self, w_lm: torch.Tensor, head_len: egtp_head, head_rem: Optional[egtp_head] = None,
-                 alpha: float = 1.0):
+                 alpha: float = 1.0, pack_w_lm: bool = True):
         cfg = egtp_config()
         cfg.vocab, cfg.d = w_lm.shape
         cfg.dtype = dtype_code(w_lm)
@@ -230,6 +245,10 @@ class Scorer:
         self.d, self.vocab, self.storage = int(cfg.d), int(cfg.vocab), w_lm.dtype
         self.ctx = egtp_create(cfg)
         self._ws = None
+        self._w_packed = None
+        if pack_w_lm and w_lm.dtype == torch.bfloat16:
+            self._w_packed = torch.empty(egtp_packed_w_lm_bytes(self.ctx), dtype=torch.uint8, device="cuda")
+            egtp_pack_w_lm(self.ctx, self._w_packed)
 
     def close(self):
         if self.ctx is not None:

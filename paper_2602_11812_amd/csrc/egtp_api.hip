@@ -17,6 +17,8 @@ struct egtp_ctx {
     hipEvent_t *prof_events;  // 2 * prof_cap events, or NULL
     int prof_cap;
     int prof_count;
+    // packed copy of W_lm for the bf16 matrix-core kernel (caller's memory), or NULL
+    const void *w_packed;
 };
 
 namespace egtp {
@@ -25,21 +27,13 @@ namespace egtp {
 static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 4096;
 static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
 
-// EGTP_K1_VARIANT (0, 1, 2) picks the matrix-core kernel's K step / ring depth (tuning knob).
-static int k1_variant_from_env()
-{
-    const char *e = getenv("EGTP_K1_VARIANT");
-    return (e && e[0] >= '0' && e[0] <= '2' && e[1] == 0) ? e[0] - '0' : 0;
-}
-
-K1Plan k1_plan(int dtype, int64_t T, int d, int V)
+K1Plan k1_plan(int dtype, int64_t T, int /*d*/, int V)
 {
     K1Plan p;
-    const bool mfma = dtype == DT_BF16 && k1_bf16_mfma_supported(d, V);
-    p.variant = mfma ? k1_variant_from_env() : -1;
-    p.tb_tokens = mfma ? BF16_TB : F32_TB;
-    p.tile_v = mfma ? BF16_TV : F32_TV;
-    const int target = mfma ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const bool bf = dtype == DT_BF16;
+    p.tb_tokens = bf ? BF16_TB : F32_TB;
+    p.tile_v = bf ? BF16_TV : F32_TV;
+    const int target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
     p.ntb = (int)((T + p.tb_tokens - 1) / p.tb_tokens);
     p.ntiles_v = (V + p.tile_v - 1) / p.tile_v;
     int ns = p.ntb > 0 ? (target + p.ntb - 1) / p.ntb : 1;
@@ -54,12 +48,12 @@ K1Plan k1_plan(int dtype, int64_t T, int d, int V)
 
 size_t k1_partial_floats(const K1Plan &p, int64_t T) { return (size_t)3 * (size_t)p.nsplit * (size_t)T; }
 
-size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V)
+size_t k1_partial_floats_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
 {
     // nsplit(T') * T' <= (target + ntb(T')) * tb_tokens for every T' <= T
-    const bool mfma = dtype == DT_BF16 && k1_bf16_mfma_supported(d, V);
-    const int64_t tbk = mfma ? BF16_TB : F32_TB;
-    const int64_t target = mfma ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const bool bf = dtype == DT_BF16;
+    const int64_t tbk = bf ? BF16_TB : F32_TB;
+    const int64_t target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
     const int64_t ntb = (T + tbk - 1) / tbk;
     return (size_t)3 * (size_t)((target + ntb) * tbk);
 }
@@ -95,6 +89,8 @@ struct Workspace {
     float *state_scale;  // [B]
     float *pool_part;    // [units_bound x d]
     float *act;          // [B x d_h_max]
+    unsigned char *hidden_packed;  // bf16 only: packed copy of this call's hidden states
+    unsigned char *w_packed;       // bf16 only, when no persistent packed W_lm was given
     size_t bytes;
 };
 
@@ -111,6 +107,13 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     w.state_scale = cv.take<float>((size_t)B);
     w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
     w.act = cv.take<float>((size_t)B * (size_t)dh);
+    w.hidden_packed = nullptr;
+    w.w_packed = nullptr;
+    if (c.dtype == EGTP_BF16) {
+        w.hidden_packed = cv.take<unsigned char>(k1_packed_bytes(T, c.d));
+        if (!ctx->w_packed)
+            w.w_packed = cv.take<unsigned char>(k1_packed_bytes(c.vocab, c.d));
+    }
     w.bytes = cv.off;
     return w;
 }
@@ -160,12 +163,21 @@ egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Work
     const egtp_config &c = ctx->cfg;
     const K1Plan p = k1_plan(c.dtype, T, c.d, c.vocab);
     const bool timed = ctx->prof_events && ctx->prof_count < ctx->prof_cap;
+    const void *wp = ctx->w_packed;
+    if (c.dtype == EGTP_BF16) {
+        if (!wp) {  // no persistent packed W_lm: pack it for this call
+            EGTP_HIP(k1_pack_rows_bf16(c.w_lm, c.vocab, c.d, w.w_packed, st));
+            wp = w.w_packed;
+        }
+        EGTP_HIP(k1_pack_rows_bf16(hidden, T, c.d, w.hidden_packed, st));
+    }
     if (timed)
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count], st));
-    if (p.variant >= 0)
-        EGTP_HIP(k1_entropy_bf16(hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
-    else
-        EGTP_HIP(k1_entropy_simple(c.dtype, hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
+    if (c.dtype == EGTP_BF16) {
+        EGTP_HIP(k1_entropy_bf16(w.hidden_packed, wp, T, c.d, c.vocab, p, w.k1_part, st));
+    } else {
+        EGTP_HIP(k1_entropy_f32(hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
+    }
     if (timed) {
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count + 1], st));
         ++ctx->prof_count;
@@ -243,8 +255,6 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
         return EGTP_ERR_SHAPE;
     if (cfg->d % (cfg->dtype == EGTP_BF16 ? 8 : 4) != 0)
         return EGTP_ERR_SHAPE;  // rows must start on 16-byte boundaries
-    if ((int64_t)cfg->d * 2 * 256 > 0x7fffffffLL)
-        return EGTP_ERR_SHAPE;  // 32-bit byte offsets inside one 256-row tile
     if (!cfg->w_lm)
         return EGTP_ERR_NULL;
     if (!(cfg->alpha > 0.0f) || !isfinite(cfg->alpha))
@@ -276,6 +286,7 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
     ctx->prof_events = nullptr;
     ctx->prof_cap = 0;
     ctx->prof_count = 0;
+    ctx->w_packed = nullptr;
     *out = ctx;
     return EGTP_OK;
 }
@@ -349,6 +360,30 @@ size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max
 }
 
 int egtp_last_hip_error(const egtp_ctx *ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+size_t egtp_packed_w_lm_bytes(const egtp_ctx *ctx)
+{
+    if (!ctx || ctx->cfg.dtype != EGTP_BF16)
+        return 0;
+    return k1_packed_bytes(ctx->cfg.vocab, ctx->cfg.d);
+}
+
+egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *stream)
+{
+    if (!ctx)
+        return EGTP_ERR_NULL;
+    if (!packed_dev) {  // forget the packed copy
+        ctx->w_packed = nullptr;
+        return EGTP_OK;
+    }
+    if (ctx->cfg.dtype != EGTP_BF16)
+        return EGTP_ERR_DTYPE;
+    if (((uintptr_t)packed_dev % ALIGN) != 0 || bytes < egtp_packed_w_lm_bytes(ctx))
+        return EGTP_ERR_WORKSPACE;
+    EGTP_HIP(k1_pack_rows_bf16(ctx->cfg.w_lm, ctx->cfg.vocab, ctx->cfg.d, packed_dev, (hipStream_t)stream));
+    ctx->w_packed = packed_dev;
+    return EGTP_OK;
+}
 
 egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_t B, int32_t *offsets_dev,
                                int32_t *seg_ids_dev, int64_t T, void *stream)

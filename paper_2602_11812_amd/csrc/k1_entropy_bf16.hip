@@ -10,11 +10,22 @@
 // H = ln S - U ln2 / S  is finished by the merge kernel from one triple per
 // (token, vocabulary range).
 //
+// Both operands are read from a PACKED copy: 256 rows x 32 K-elements per block of 16 KiB,
+// stored exactly as the block sits in LDS (16-byte chunks XOR-swizzled by row so that the
+// MFMA fragment reads are conflict-free).  A K step of a tile is then one contiguous
+// 16 KiB read, which is what HBM and the Infinity Cache want; reading 64-byte row pieces
+// with a row stride of 2d bytes from the row-major matrices stalls the ring on DRAM page
+// misses.  pack_rows_bf16 builds the packed copy (W_lm once, hidden states once per call;
+// rows and K are zero-padded to whole blocks).
+//
 // Workgroup = 256 threads = 4 waves (2 along vocabulary x 2 along tokens), macro tile
 // 256 vocabulary rows x 256 tokens, each wave 128 x 128 = 4x4 MFMA 32x32x16 tiles
-// (256 accumulator registers).  Operand tiles go from global memory straight into LDS
-// (16 bytes per lane, no staging registers) through an NSTAGE-deep ring of K steps;
-// 16-byte chunks are XOR-swizzled by row so that the MFMA fragment reads are conflict-free.
+// (256 accumulator registers).  Blocks go from global memory straight into an NSTAGE-deep
+// LDS ring (16 bytes per lane, no staging registers).  One wave per SIMD means nothing
+// hides a stall, so the instruction order inside a K step is pinned: every MFMA is followed
+// by one load or one fragment read, which then issues in the shadow of the MFMA.  The one
+// barrier per step sits between the two K sub-steps, after the reads of the current stage
+// and before the fragments of the next step are fetched.
 #include "kernels.h"
 
 namespace egtp {
@@ -24,11 +35,18 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace {
 
-constexpr int BM = 256;      // vocabulary rows per tile
-constexpr int BN = 256;      // tokens per block
-constexpr int TB_GROUP = 8;  // token blocks that sweep the same vocabulary range together
+constexpr int BM = 256;        // vocabulary rows per tile
+constexpr int BN = 256;        // tokens per block
+constexpr int BK = K1_PACK_K;  // K elements per step (32)
+constexpr int ROW_BYTES = BK * 2;
+constexpr int TILE_BYTES = 256 * ROW_BYTES;  // one operand block, 16 KiB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // W block + hidden block
+constexpr int NPASS = TILE_BYTES / 4096;     // 16-byte loads per lane and operand block (4)
+constexpr int LOADS_PER_STEP = 2 * NPASS;
+constexpr int TB_GROUP = 8;    // token blocks that sweep the same vocabulary range together
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float LOG2E = 1.4426950408889634f;
+static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geometry");
 
 struct Stats {
     float m, S, U;
@@ -50,18 +68,17 @@ __device__ __forceinline__ Stats merge(Stats a, Stats b)
 }
 
 // Fold the 16 logits a lane holds for one token column in one MFMA tile into the running
-// statistics of that token.  MASK: only vocabulary rows >= row_lo count (the last tile of a
-// ragged vocabulary is loaded shifted back so that it ends at V; its leading rows belong to
-// the tile before).  row0 is the vocabulary row of element 0 for this lane.
+// statistics of that token.  MASK: only vocabulary rows < V count (the zero rows that pad
+// the last tile are excluded).  row0 is the vocabulary row of element 0 for this lane.
 template <bool MASK>
-__device__ __forceinline__ void fold_tile(const f32x16 &a, Stats &st, int row0, int row_lo)
+__device__ __forceinline__ void fold_tile(const f32x16 &a, Stats &st, int row0, int V)
 {
     float z[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         float v = a[i];
         if (MASK)
-            v = (row0 + 8 * (i >> 2) + (i & 3)) >= row_lo ? v : NEG_BIG;
+            v = (row0 + 8 * (i >> 2) + (i & 3)) < V ? v : NEG_BIG;
         z[i] = v;
     }
     float mx = z[0];
@@ -110,33 +127,26 @@ __device__ __forceinline__ void load16_to_lds(const unsigned char *g, unsigned c
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
-template <int BK, int NSTAGE>
+// scheduling-group masks of the AMDGPU backend
+constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100;
+
+template <int NSTAGE>
 __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
-    const unsigned char *__restrict__ Wb, const unsigned char *__restrict__ Hb, long T, int d, int V,
+    const unsigned char *__restrict__ Wp, const unsigned char *__restrict__ Hp, long T, int KT, int V,
     int ntb, int nsplit, int tps, int ntiles_v, float *__restrict__ part)
 {
-    constexpr int ROW_BYTES = BK * 2;             // bytes of one tile row in LDS
-    constexpr int CPR = ROW_BYTES / 16;           // 16-byte chunks per row (8 or 4)
-    constexpr int TILE_BYTES = 256 * ROW_BYTES;   // one operand tile
-    constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // A + B
-    constexpr int ROWS_PER_WAVE_LOAD = 64 / CPR;  // rows covered by one wave-wide 1 KiB load
-    constexpr int NPASS = 256 / (4 * ROWS_PER_WAVE_LOAD);  // loads per lane, operand and K step
-    constexpr int KK = BK / 16;                   // MFMA K sub-steps per K step
-    constexpr int LOADS_PER_STEP = 2 * NPASS;
-    static_assert(BK == 64 || BK == 32, "K step");
-    static_assert((NSTAGE - 2) * LOADS_PER_STEP < 64, "vmcnt range");
-
+    static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LOADS_PER_STEP < 64, "ring depth");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1;  // vocabulary half of the macro tile
     const int wn = wave & 1;   // token half
 
     // ---- which (token block, vocabulary range) this workgroup owns -------------------
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
-    // logical units so that neighbours in time share W_lm tiles and token blocks in its L2.
+    // logical units so that neighbours in time share W_lm blocks and token blocks in its L2.
     int tb, sp;
     {
         const int units = gridDim.x;
@@ -154,58 +164,32 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     const int vt_begin = sp * tps;
     const int vt_end = min(ntiles_v, vt_begin + tps);
     const long tok0 = (long)tb * BN;
-    const long row_bytes = (long)d * 2;
-    const int KT = d / BK;  // d is a multiple of BK (checked by the launcher)
+    const int total = (vt_end - vt_begin) * KT;
 
-    // ---- global -> LDS geometry ----------------------------------------------------------
-    // One wave-wide load fills 1 KiB of LDS = ROWS_PER_WAVE_LOAD rows; pass p of wave w fills
-    // rows (p*4 + w) * ROWS_PER_WAVE_LOAD ...  Lane l sits at row lr = l / CPR, chunk slot
-    // l % CPR of that block and therefore fetches the logical chunk (slot ^ swizzle(row)).
-    const int lr = lane / CPR;
-    const int slot = lane % CPR;
-    const int row_in_tile0 = wave * ROWS_PER_WAVE_LOAD + lr;  // + p * 4 * ROWS_PER_WAVE_LOAD
-    const int sw0 = CPR == 8 ? (row_in_tile0 & 7) : ((row_in_tile0 >> 1) & 3);
-    const unsigned chunk_bytes = (unsigned)((slot ^ sw0) * 16);
-    // (p * 4 * ROWS_PER_WAVE_LOAD is a multiple of 16, so the swizzle term does not depend on p)
-    const unsigned offA0 = (unsigned)(row_in_tile0 * row_bytes) + chunk_bytes;
-    const long passA = (long)(4 * ROWS_PER_WAVE_LOAD) * row_bytes;
-    const unsigned char *Hblk = Hb + tok0 * row_bytes;
-    unsigned offB[NPASS];
-    {
-        const long last = T - 1 - tok0;  // >= 0: the block holds at least one token
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            long rr = row_in_tile0 + p * 4 * ROWS_PER_WAVE_LOAD;
-            rr = rr < last ? rr : last;  // rows past the end re-read the last token (discarded)
-            offB[p] = (unsigned)(rr * row_bytes) + chunk_bytes;
-        }
-    }
-    unsigned char *lds_wave = smem + wave * 1024;  // + stage * STAGE_BYTES + p * 4096 (+ TILE_BYTES for B)
-
-    // tile vt starts at vocabulary row min(vt * BM, V - BM): the last tile of a ragged
-    // vocabulary is shifted back (V >= BM is checked by the launcher)
+    // ---- global -> LDS: a block is copied linearly, 1 KiB per wave-wide load ------------
+    const unsigned lane_off = (unsigned)(wave * 1024 + lane * 16);
+    const unsigned char *Hblk = Hp + (long)tb * KT * TILE_BYTES + lane_off;
+    const unsigned char *Wl = Wp + lane_off;
+    unsigned char *lds_wave = smem + wave * 1024;
     auto issue_loads = [&](int vt, int kt, int stage) {
-        const int v0 = min(vt * BM, V - BM);
-        const unsigned char *Wt = Wb + (long)v0 * row_bytes + (long)kt * ROW_BYTES;
-        const unsigned char *Ht = Hblk + (long)kt * ROW_BYTES;
+        const unsigned char *Wt = Wl + ((long)vt * KT + kt) * TILE_BYTES;
+        const unsigned char *Ht = Hblk + (long)kt * TILE_BYTES;
         unsigned char *dst = lds_wave + stage * STAGE_BYTES;
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            load16_to_lds(Wt + p * passA + offA0, dst + p * 4096);
-            load16_to_lds(Ht + offB[p], dst + TILE_BYTES + p * 4096);
+            load16_to_lds(Wt + p * 4096, dst + p * 4096);
+            load16_to_lds(Ht + p * 4096, dst + TILE_BYTES + p * 4096);
         }
     };
 
-    // ---- fragment read geometry --------------------------------------------------------
+    // ---- fragment read geometry (row r, chunk c sits at r*64 + ((c ^ ((r>>1)&3)) * 16)) ----
     const int l31 = lane & 31;
     const int khalf = lane >> 5;
     const unsigned fragA = (unsigned)(wm * 128 + l31) * ROW_BYTES;
     const unsigned fragB = (unsigned)TILE_BYTES + (unsigned)(wn * 128 + l31) * ROW_BYTES;
-    const int swf = CPR == 8 ? (l31 & 7) : ((l31 >> 1) & 3);
-    unsigned swz[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-        swz[kk] = (unsigned)(((kk * 2 + khalf) ^ swf) << 4);
+    const int swf = (l31 >> 1) & 3;
+    const unsigned swz0 = (unsigned)(((0 + khalf) ^ swf) << 4);
+    const unsigned swz1 = (unsigned)(((2 + khalf) ^ swf) << 4);
 
     Stats st[4];
 #pragma unroll
@@ -215,28 +199,45 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         st[ni].U = 0.f;
     }
 
-    const int total = (vt_end - vt_begin) * KT;
-
-    // ---- prologue: fill NSTAGE-1 stages -------------------------------------------------
-    int lvt = vt_begin, lkt = 0, lstep = 0;  // the load stream's position
+    // The load stream runs NSTAGE-1 steps ahead of the MFMAs.  Past the end it keeps
+    // re-reading the last step (same addresses, into a stage nobody reads any more), so
+    // every step issues the same number of loads and one wait constant serves the sweep.
+    int lvt = vt_begin, lkt = 0, lstep = 0;
+    auto advance_ld = [&]() {  // branch-free: a step must stay one scheduling region
+        const int adv = lstep + 1 < total ? 1 : 0;
+        lstep += adv;
+        const int nk = lkt + adv;
+        const int wrap = nk == KT ? 1 : 0;
+        lkt = wrap ? 0 : nk;
+        lvt += wrap;
+    };
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) {
-        if (lstep < total) {
-            issue_loads(lvt, lkt, s);
-            ++lstep;
-            if (++lkt == KT) {
-                lkt = 0;
-                ++lvt;
-            }
-        }
+        issue_loads(lvt, lkt, s);
+        advance_ld();
     }
-    if (total <= NSTAGE - 1)
-        wait_vmcnt<0>();
-    else
-        wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();
+    wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
 
-    int it = 0;
+    bf16x8 fa[2][4], fb[2][4];
+#define EGTP_READ_FRAGS(set_, stage_base_, swz_)                                                  \
+    {                                                                                             \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                          \
+            fa[set_][mi] = *(const bf16x8 *)((stage_base_) + fragA + mi * 32 * ROW_BYTES + swz_); \
+        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                          \
+            fb[set_][ni] = *(const bf16x8 *)((stage_base_) + fragB + ni * 32 * ROW_BYTES + swz_); \
+    }
+#define EGTP_MFMA_PHASE(set_)                                                                     \
+    {                                                                                             \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                          \
+            _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                      \
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set_][mi], fb[set_][ni], \
+                                                                      acc[mi][ni], 0, 0, 0);      \
+    }
+    EGTP_READ_FRAGS(0, smem, swz0);
+
+    int ldstage = NSTAGE - 1;  // stage the next loads go to
+    int cstage = 0;            // stage being consumed
     for (int vt = vt_begin; vt < vt_end; ++vt) {
         f32x16 acc[4][4];
 #pragma unroll
@@ -247,62 +248,65 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
                 for (int i = 0; i < 16; ++i)
                     acc[mi][ni][i] = 0.f;
 
-        for (int kt = 0; kt < KT; ++kt, ++it) {
-            // refill the stage that was consumed in the previous iteration
-            if (lstep < total) {
-                issue_loads(lvt, lkt, lstep % NSTAGE);
-                ++lstep;
-                if (++lkt == KT) {
-                    lkt = 0;
-                    ++lvt;
-                }
+        for (int kt = 0; kt < KT; ++kt) {
+            const unsigned char *sA = smem + cstage * STAGE_BYTES;
+            const int nstage = cstage + 1 == NSTAGE ? 0 : cstage + 1;
+            const unsigned char *sN = smem + nstage * STAGE_BYTES;
+            // ---- first half: loads for the step NSTAGE-1 ahead (into the stage consumed in
+            //      the previous step), fragments of sub-step 1, MFMAs of sub-step 0
+            issue_loads(lvt, lkt, ldstage);
+            advance_ld();
+            ldstage = ldstage + 1 == NSTAGE ? 0 : ldstage + 1;
+            EGTP_READ_FRAGS(1, sA, swz1);
+            EGTP_MFMA_PHASE(0);
+#pragma unroll
+            for (int j = 0; j < LOADS_PER_STEP; ++j) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, 1, 0);
             }
-            const unsigned char *sA = smem + (it % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                bf16x8 af[4], bfr[4];
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-                    af[mi] = *(const bf16x8 *)(sA + fragA + mi * 32 * ROW_BYTES + swz[kk]);
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    bfr[ni] = *(const bf16x8 *)(sA + fragB + ni * 32 * ROW_BYTES + swz[kk]);
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < 4; ++ni)
-                        acc[mi][ni] =
-                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+            for (int j = 0; j < 8; ++j) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
             }
-            // the next step's tile must have landed (own loads), then everyone's
-            if (lstep - (it + 1) >= NSTAGE - 1)
-                wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();
-            else
-                wait_vmcnt<0>();
-            // A bare barrier: every LDS read of this step has already been consumed by an
-            // MFMA, and the direct-to-LDS loads are ordered by the explicit counter waits
-            // above, so no memory fence (which would drain the whole load ring) is needed.
+            // ---- the next step's blocks have landed (own loads; the newest NSTAGE-2 steps may
+            //      still be in flight), then everyone's.  Every read of the current stage has
+            //      been consumed by now.  A bare barrier: a fence would drain the whole ring.
+            wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();
             __builtin_amdgcn_s_barrier();
+            // ---- second half: fragments of the next step's sub-step 0, MFMAs of sub-step 1
+            EGTP_READ_FRAGS(0, sN, swz0);
+            EGTP_MFMA_PHASE(1);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+            }
+            cstage = nstage;
         }
 
         // a full tile of logits is in registers: fold it into the statistics and forget it
-        const int v0 = min(vt * BM, V - BM);
-        const int row_base = v0 + wm * 128 + 4 * khalf;
-        const int row_lo = vt * BM;
-        if (v0 < row_lo) {
+        const int row_base = vt * BM + wm * 128 + 4 * khalf;
+        if (vt * BM + BM > V) {
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni)
-                    fold_tile<true>(acc[mi][ni], st[ni], row_base + mi * 32, row_lo);
+                    fold_tile<true>(acc[mi][ni], st[ni], row_base + mi * 32, V);
         } else {
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni)
-                    fold_tile<false>(acc[mi][ni], st[ni], row_base + mi * 32, row_lo);
+                    fold_tile<false>(acc[mi][ni], st[ni], row_base + mi * 32, V);
         }
     }
+#undef EGTP_READ_FRAGS
+#undef EGTP_MFMA_PHASE
+
+    // drain the ring (the tail re-reads) before its memory is reused
+    wait_vmcnt<0>();
+    __syncthreads();
 
     // ---- combine the lanes and waves that hold the same token ----------------------------
 #pragma unroll
@@ -313,7 +317,7 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         o.U = __shfl_xor(st[ni].U, 32);
         st[ni] = merge(st[ni], o);
     }
-    float *red = (float *)smem;  // [wn][ni][32][3]; the main loop ended on a barrier
+    float *red = (float *)smem;  // [wn][ni][32][3]
     if (wm == 1 && lane < 32) {
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) {
@@ -368,44 +372,76 @@ __global__ __launch_bounds__(256) void k1_merge_kernel(const float *__restrict__
     entropy[t] = logf(a.S) - a.U * 0.6931471805599453f / a.S;
 }
 
-template <int BK, int NSTAGE>
-hipError_t launch(const void *hidden, const void *w_lm, int64_t T, int d, int V, const K1Plan &p, float *part,
-                  hipStream_t st)
+// Packs rows of a row-major bf16 matrix src[R x d] into blocks of 256 rows x 32 K-elements in
+// LDS-image order; rows >= R and K >= d are zero.  One workgroup packs 8 consecutive K steps
+// of one row tile: a wave reads 512 contiguous bytes of each of two rows at a time.
+__global__ __launch_bounds__(256) void pack_rows_bf16_kernel(const unsigned char *__restrict__ src, long R,
+                                                             int d, int KT, unsigned char *__restrict__ dst)
 {
-    constexpr int LDS_BYTES = NSTAGE * 2 * 256 * BK * 2;
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    const long tile = blockIdx.x;
+    const int ks0 = blockIdx.y * 8;
+    const int c32 = threadIdx.x & 31;   // 16-byte chunk of the 512-byte span: K step c32/4, chunk c32%4
+    const int rsub = threadIdx.x >> 5;  // 8 rows per pass
+    const int ks = ks0 + (c32 >> 2);
+    const int chunk = c32 & 3;
+    const long k_elem = (long)ks * BK + chunk * 8;
+    if (ks >= KT)
+        return;
+    unsigned char *blk = dst + (tile * KT + ks) * (long)TILE_BYTES;
+    for (int r = rsub; r < 256; r += 8) {
+        const long row = tile * 256 + r;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < R && k_elem < d)
+            v = *(const uint4 *)(src + (row * d + k_elem) * 2);
+        *(uint4 *)(blk + r * ROW_BYTES + ((chunk ^ ((r >> 1) & 3)) << 4)) = v;
+    }
+}
+
+}  // namespace
+
+size_t k1_packed_bytes(int64_t rows, int d)
+{
+    const int64_t tiles = (rows + 255) / 256;
+    const int64_t kt = (d + BK - 1) / BK;
+    return (size_t)(tiles * kt) * TILE_BYTES;
+}
+
+hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hipStream_t st)
+{
+    if (rows <= 0)
+        return hipSuccess;
+    const long tiles = (rows + 255) / 256;
+    const int kt = (d + BK - 1) / BK;
+    if (tiles > 0x7fffffffL)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pack_rows_bf16_kernel, dim3((unsigned)tiles, (kt + 7) / 8), dim3(256), 0, st,
+                       (const unsigned char *)src, (long)rows, d, kt, (unsigned char *)dst);
+    return hipGetLastError();
+}
+
+hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
+                           const K1Plan &p, float *part, hipStream_t st)
+{
+    constexpr int NSTAGE = 4;
+    constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k1_entropy_bf16_kernel<BK, NSTAGE>,
+        hipError_t e = hipFuncSetAttribute((const void *)k1_entropy_bf16_kernel<NSTAGE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess)
             return e;
         attr_set = true;
     }
-    const long units = (long)p.ntb * p.nsplit;
-    hipLaunchKernelGGL((k1_entropy_bf16_kernel<BK, NSTAGE>), dim3((unsigned)units), dim3(256), LDS_BYTES, st,
-                       (const unsigned char *)w_lm, (const unsigned char *)hidden, (long)T, d, V, p.ntb,
-                       p.nsplit, p.tiles_per_split, p.ntiles_v, part);
-    return hipGetLastError();
-}
-
-}  // namespace
-
-bool k1_bf16_mfma_supported(int d, int V) { return d % 64 == 0 && V >= BM; }
-
-hipError_t k1_entropy_bf16(const void *hidden, const void *w_lm, int64_t T, int d, int V,
-                           const K1Plan &p, float *part, hipStream_t st)
-{
-    if (p.tb_tokens != BN || p.tile_v != BM || !k1_bf16_mfma_supported(d, V) || T <= 0)
+    if (p.tb_tokens != BN || p.tile_v != BM || T <= 0)
         return hipErrorInvalidValue;
     const long units = (long)p.ntb * p.nsplit;
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
-    switch (p.variant) {
-    case 1: return launch<32, 4>(hidden, w_lm, T, d, V, p, part, st);
-    case 2: return launch<32, 3>(hidden, w_lm, T, d, V, p, part, st);
-    default: return launch<64, 2>(hidden, w_lm, T, d, V, p, part, st);
-    }
+    const int kt = (d + BK - 1) / BK;
+    hipLaunchKernelGGL((k1_entropy_bf16_kernel<NSTAGE>), dim3((unsigned)units), dim3(256), LDS_BYTES, st,
+                       (const unsigned char *)w_packed, (const unsigned char *)hidden_packed, (long)T, kt, V,
+                       p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part);
+    return hipGetLastError();
 }
 
 hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st)

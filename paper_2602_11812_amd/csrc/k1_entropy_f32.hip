@@ -1,10 +1,8 @@
-// Fused LM-head contraction + streaming entropy (Eq. 2) with plain fp32 FMAs: the path for
-// fp32 inputs, and for bf16 shapes that the matrix-core kernel does not take (hidden size
-// not a multiple of 64, vocabulary below one tile).
+// Fused LM-head contraction + streaming entropy for fp32 inputs (Eq. 2), plain fp32 FMAs.
 //
-// These are small, exactness-oriented workloads, so this kernel is a straightforward
-// LDS-tiled contraction: a 64-token x 64-vocabulary tile per workgroup, 4 x 4 logits per
-// thread, K step 16.  As in the bf16 kernel the logits are folded into
+// The fp32 storage type serves small, exactness-oriented workloads, so this kernel is a
+// straightforward LDS-tiled contraction: a 64-token x 64-vocabulary tile per workgroup,
+// 4 x 4 logits per thread, K step 16.  As in the bf16 kernel the logits are folded into
 // per-token running statistics (m, S, U) as soon as a vocabulary tile is finished and are
 // never stored; the same merge kernel finishes H = ln S - U ln2 / S.
 #include "kernels.h"
@@ -35,21 +33,8 @@ __device__ __forceinline__ Stats merge(Stats a, Stats b)
     return r;
 }
 
-// four consecutive elements along K, widened to fp32
-template <bool BF16>
-__device__ __forceinline__ float4 load4(const void *base, long elem)
-{
-    if (BF16) {
-        const uint2 q = *(const uint2 *)((const unsigned short *)base + elem);
-        return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xffff0000u),
-                           __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xffff0000u));
-    }
-    return *(const float4 *)((const float *)base + elem);
-}
-
-template <bool BF16>
-__global__ __launch_bounds__(256) void k1_entropy_simple_kernel(
-    const void *__restrict__ W, const void *__restrict__ Hd, long T, int d, int V, int ntb,
+__global__ __launch_bounds__(256) void k1_entropy_f32_kernel(
+    const float *__restrict__ W, const float *__restrict__ Hd, long T, int d, int V, int ntb,
     int nsplit, int tps, int ntiles_v, float *__restrict__ part)
 {
     __shared__ float As[TK][TM + PAD];  // As[k][vocab row]
@@ -95,8 +80,8 @@ __global__ __launch_bounds__(256) void k1_entropy_simple_kernel(
         for (int k0 = 0; k0 < d; k0 += TK) {
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
             if (k0 + lk < d) {
-                a = load4<BF16>(W, wrow + k0 + lk);
-                b = load4<BF16>(Hd, hrow + k0 + lk);
+                a = *(const float4 *)(W + wrow + k0 + lk);
+                b = *(const float4 *)(Hd + hrow + k0 + lk);
             }
             __syncthreads();  // previous step's readers are done
             As[lk + 0][lrow] = a.x;
@@ -179,20 +164,17 @@ __global__ __launch_bounds__(256) void k1_entropy_simple_kernel(
 
 }  // namespace
 
-hipError_t k1_entropy_simple(int dtype, const void *hidden, const void *w_lm, int64_t T, int d, int V,
-                             const K1Plan &p, float *part, hipStream_t st)
+hipError_t k1_entropy_f32(const void *hidden, const void *w_lm, int64_t T, int d, int V,
+                          const K1Plan &p, float *part, hipStream_t st)
 {
     if (p.tb_tokens != TN || p.tile_v != TM || T <= 0)
         return hipErrorInvalidValue;
     const long units = (long)p.ntb * p.nsplit;
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
-    if (dtype == DT_BF16)
-        hipLaunchKernelGGL(k1_entropy_simple_kernel<true>, dim3((unsigned)units), dim3(256), 0, st, w_lm,
-                           hidden, (long)T, d, V, p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part);
-    else
-        hipLaunchKernelGGL(k1_entropy_simple_kernel<false>, dim3((unsigned)units), dim3(256), 0, st, w_lm,
-                           hidden, (long)T, d, V, p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part);
+    hipLaunchKernelGGL(k1_entropy_f32_kernel, dim3((unsigned)units), dim3(256), 0, st, (const float *)w_lm,
+                       (const float *)hidden, (long)T, d, V, p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v,
+                       part);
     return hipGetLastError();
 }
 

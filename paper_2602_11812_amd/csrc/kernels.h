@@ -20,12 +20,7 @@ struct K1Plan {
     int ntiles_v;         // vocabulary tiles in total
     int nsplit;           // vocabulary ranges
     int tiles_per_split;  // tiles per range (last range may hold fewer)
-    int variant;          // kernel flavour: 0 = matrix-core kernel, K step 64, 2 LDS stages; 1 = K step 32,
-                          // 4 stages; 2 = K step 32, 3 stages; -1 = plain FMA kernel
 };
-
-// true when the matrix-core kernel can take this shape (else the plain FMA kernel runs)
-bool k1_bf16_mfma_supported(int d, int V);
 
 K1Plan k1_plan(int dtype, int64_t T, int d, int V);
 // floats needed for the partial triples of a plan (3 * nsplit * T)
@@ -33,12 +28,21 @@ size_t k1_partial_floats(const K1Plan &p, int64_t T);
 // upper bound of k1_partial_floats over every T' <= T
 size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
 
+// Packed operand layout of the bf16 matrix-core kernel: blocks of 256 rows x K1_PACK_K
+// elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * ceil(d/K) + step,
+// stored in LDS-image order; rows and K zero-padded to whole blocks.
+constexpr int K1_PACK_K = 32;
+constexpr int K1_PACK_BLOCK_BYTES = 256 * K1_PACK_K * 2;
+size_t k1_packed_bytes(int64_t rows, int d);
+hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hipStream_t st);
+
 // Eq. 2, fused: partial (max, sum e^{z-m}, sum e^{z-m}(z-m) log2 e) per token and vocabulary range.
-hipError_t k1_entropy_bf16(const void *hidden, const void *w_lm, int64_t T, int d, int V,
+// bf16: both operands in the packed layout.
+hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
                            const K1Plan &p, float *part, hipStream_t st);
-// plain fp32-FMA kernel for fp32 inputs and for bf16 shapes the matrix-core kernel does not take
-hipError_t k1_entropy_simple(int dtype, const void *hidden, const void *w_lm, int64_t T, int d, int V,
-                             const K1Plan &p, float *part, hipStream_t st);
+// fp32 inputs (row-major), plain fp32 FMAs
+hipError_t k1_entropy_f32(const void *hidden, const void *w_lm, int64_t T, int d, int V,
+                          const K1Plan &p, float *part, hipStream_t st);
 // merges the nsplit partial triples of each token in a fixed order; entropy[t] = ln S - U/S
 hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st);
 

@@ -26,12 +26,12 @@ def _np(d):
     return {k: v.cpu().numpy() for k, v in d.items()}
 
 
-def _scorer(gpu, w, alpha=1.0, b1=None, b2=None, w2=None, centers=None, head_rem=None):
+def _scorer(gpu, w, alpha=1.0, b1=None, b2=None, w2=None, centers=None, head_rem=None, pack_w_lm=True):
     td = gpu.to_device
     head = gpu.make_head(td(w.w1), td(w.w2 if w2 is None else w2),
                          None if b1 is None else td(b1), None if b2 is None else td(b2),
                          None if centers is None else td(centers))
-    return gpu.Scorer(td(w.w_lm), head, head_rem, alpha)
+    return gpu.Scorer(td(w.w_lm), head, head_rem, alpha, pack_w_lm)
 
 
 def _offsets_on_gpu(gpu, sc, lengths, want_seg=False):
@@ -80,20 +80,21 @@ def _small_bf16(seed=1, B=6, d=512, V=2500, d_h=96, lengths=None, lo=16, hi=400)
     return wl.make(spec)
 
 
-@pytest.mark.parametrize("variant", ["0", "1", "2"])
-def test_bf16_mfma_several_tiles_and_ragged_tails(gpu, variant, monkeypatch):
+@pytest.mark.parametrize("pack_w_lm", [True, False])
+def test_bf16_mfma_several_tiles_and_ragged_tails(gpu, pack_w_lm):
     # V = 2500 -> 10 vocabulary tiles, the last one ragged; T spans several 256-token blocks
-    # with a ragged last block; d = 512 -> 8 (or 16) K steps through the LDS ring
-    monkeypatch.setenv("EGTP_K1_VARIANT", variant)
+    # with a ragged last block; d = 512 -> 16 K steps through the LDS ring.  W_lm is packed
+    # once up front, or re-packed into the workspace by the call itself.
     w = _small_bf16()
     assert w.T > 600 and w.T % 256 != 0
-    got = _run(gpu, w)
+    got = _run(gpu, w, pack_w_lm=pack_w_lm)
     off = oracle.offsets_from_lengths(w.lengths)
     want = oracle.egtp(w.hidden, off, w.w_lm, oracle.Head(w.w1, w.w2))
     assert_egtp_close(got, want)
 
 
-@pytest.mark.parametrize("T,V,d", [(1, 256, 64), (255, 257, 64), (256, 511, 128), (257, 512, 192), (513, 1000, 320)])
+@pytest.mark.parametrize("T,V,d", [(1, 256, 64), (255, 257, 64), (256, 511, 128), (257, 512, 192), (513, 1000, 320),
+                                   (300, 769, 96), (2, 255, 32)])
 def test_bf16_mfma_edge_sizes(gpu, T, V, d):
     w = _small_bf16(seed=7, B=1, d=d, V=V, d_h=8, lengths=(T,))
     got = _run(gpu, w)
@@ -101,9 +102,10 @@ def test_bf16_mfma_edge_sizes(gpu, T, V, d):
     assert_egtp_close(got, want)
 
 
-def test_bf16_plain_kernel_for_unaligned_shapes(gpu):
-    # d not a multiple of 64 and a vocabulary below one tile take the plain FMA kernel
-    for d, V in ((72, 100), (128, 200), (40, 3000)):
+def test_bf16_shapes_that_need_padding(gpu):
+    # hidden size not a multiple of the 32-element K step, vocabulary below one 256-row tile:
+    # the packed copies are zero-padded and the padded vocabulary rows masked
+    for d, V in ((72, 100), (128, 200), (40, 3000), (8, 1)):
         w = _small_bf16(seed=3, B=3, d=d, V=V, d_h=16, lengths=(5, 70, 1))
         got = _run(gpu, w)
         want = oracle.egtp(w.hidden, [0, 5, 75, 76], w.w_lm, oracle.Head(w.w1, w.w2))
