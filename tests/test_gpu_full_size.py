@@ -1,0 +1,132 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The fp64 oracle cannot sweep a 137k-token x 152k-vocabulary batch, so the comparison is on
+sampled outputs it can compute one by one (per-token entropies; whole short sequences end to
+end) plus a decoupled check of pooling and head on ALL sequences: the oracle's Eq. 3-4 and head
+run in fp64 on the GPU's own entropies (O(T d) work).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import (TOL_ENTROPY_ABS, TOL_LSE_ABS, TOL_POOLED_REL_L2, assert_pred_close, rel_l2)
+from paper_2602_11812_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2602_11812_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load_library()
+    return binding
+
+
+def _score_full(gpu, w):
+    import torch
+    td = gpu.to_device
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    off = sc.build_offsets(torch.from_numpy(w.lengths).cuda(), w.T)
+    out = {k: v.cpu().numpy() for k, v in sc.score(td(w.hidden), off).items()}
+    return sc, off.cpu().numpy(), out
+
+
+def _check_sampled(w, off, out, n_seq_sampled, n_short):
+    B = w.spec.B
+    rng = np.random.default_rng(12345)
+    ooff = oracle.offsets_from_lengths(w.lengths)
+    assert np.array_equal(off, ooff)                                   # integer work: bit exact
+    head = oracle.Head(w.w1, w.w2)
+
+    # (1) sampled tokens: first, last and two random tokens of some sequences
+    seqs = rng.choice(B, size=min(n_seq_sampled, B), replace=False)
+    toks = []
+    for b in seqs:
+        lo, hi = int(ooff[b]), int(ooff[b + 1])
+        toks += [lo, hi - 1] + rng.integers(lo, hi, size=2).tolist()
+    toks = np.unique(np.asarray(toks))
+    H = oracle.entropy(np.ascontiguousarray(w.hidden[toks]), w.w_lm)
+    err = np.abs(out["entropy"][toks].astype(np.float64) - H)
+    assert err.max() <= TOL_ENTROPY_ABS, f"sampled entropy err {err.max()}"
+
+    # (2) the shortest sequences end to end (entropy -> weights -> pooled -> prediction)
+    short = np.argsort(w.lengths, kind="stable")[:n_short]
+    for b in short:
+        lo, hi = int(ooff[b]), int(ooff[b + 1])
+        r = oracle.egtp(np.ascontiguousarray(w.hidden[lo:hi]), [0, hi - lo], w.w_lm, head)
+        assert np.abs(out["entropy"][lo:hi] - r.entropy).max() <= TOL_ENTROPY_ABS
+        assert rel_l2(out["pooled"][b], r.pooled[0]) <= TOL_POOLED_REL_L2
+        assert abs(out["lse"][b] - r.lse[0]) <= TOL_LSE_ABS
+    # predictions of those sequences, judged on the scale of the whole batch (see below)
+
+    # (3) every sequence: fp64 pooling + head on the GPU's entropies
+    _, pooled, lse = oracle.pool(w.hidden, out["entropy"].astype(np.float64), ooff)
+    worst = max(rel_l2(out["pooled"][b], pooled[b]) for b in range(B))
+    assert worst <= TOL_POOLED_REL_L2, f"pooled rel L2 {worst}"
+    assert np.abs(out["lse"].astype(np.float64) - lse).max() <= TOL_LSE_ABS
+    assert_pred_close(out["pred"], oracle.predict(pooled, head))
+
+    # properties that hold at any size
+    lnV = math.log(w.spec.V)
+    assert np.all(out["entropy"] > 0) and np.all(out["entropy"] <= lnV + 1e-4)
+    n = w.lengths.astype(np.float64)
+    assert np.all(out["lse"] >= np.log(n) - 1e-3) and np.all(out["lse"] <= np.log(n) + lnV + 1e-3)
+
+
+def test_serving_workload_full_size(gpu):
+    w = wl.make(wl.SPECS["serving"])
+    assert w.T == 137720 and w.spec.V == 151936 and w.spec.d == 4096
+    sc, off, out = _score_full(gpu, w)
+    _check_sampled(w, off, out, n_seq_sampled=24, n_short=2)
+    sc.close()
+
+
+def test_mid_workload_full_size(gpu):
+    w = wl.make(wl.SPECS["mid"])
+    sc, off, out = _score_full(gpu, w)
+    _check_sampled(w, off, out, n_seq_sampled=32, n_short=4)
+    sc.close()
+
+
+def test_plp_decode_full_batch(gpu):
+    # 512 live sequences, one token each per step, full d and V; three steps from the empty state
+    import torch
+    spec = wl.SPECS["plp_decode"]
+    w = wl.make(spec)                       # W_lm and head of the decode workload (the draw's
+    td = gpu.to_device                      # own hidden states serve as step 0 and are unused)
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    B, d, steps = spec.B, spec.d, 3
+    pooled = torch.zeros(B, d, dtype=torch.float32, device="cuda")
+    lse = torch.full((B,), -math.inf, dtype=torch.float32, device="cuda")
+    gen = [wl.decode_hidden(spec, t + 1) for t in range(steps)]
+    ents, preds = [], []
+    for g in gen:
+        ent = torch.empty(B, dtype=torch.float32, device="cuda")
+        preds.append(sc.step(td(g), pooled, lse, entropy_out=ent).cpu().numpy())
+        ents.append(ent.cpu().numpy())
+    pooled_np, lse_np = pooled.cpu().numpy(), lse.cpu().numpy()
+    head = oracle.Head(w.w1, w.w2)
+
+    # sampled sequences against the recompute-from-history oracle
+    pick = np.random.default_rng(7).choice(B, size=6, replace=False)
+    sub = [np.ascontiguousarray(g[pick]) for g in gen]
+    want = oracle.plp(np.zeros((0, d), np.uint16), np.zeros(len(pick) + 1, np.int32), sub, w.w_lm, head)
+    for t in range(steps):
+        newest = np.arange(len(pick)) * (t + 1) + t          # last token of each sampled sequence
+        assert np.abs(ents[t][pick] - want[t].entropy[newest]).max() <= TOL_ENTROPY_ABS
+    for i, b in enumerate(pick):
+        assert rel_l2(pooled_np[b], want[-1].pooled[i]) <= TOL_POOLED_REL_L2
+        assert abs(lse_np[b] - want[-1].lse[i]) <= TOL_LSE_ABS
+
+    # every sequence: fp64 fold of the GPU's entropies, then the head
+    cat = np.stack(gen, axis=1).reshape(B * steps, d)        # sequence-major: tokens 1..steps of each
+    Hg = np.stack(ents, axis=1).reshape(B * steps).astype(np.float64)
+    _, p64, l64 = oracle.pool(cat, Hg, np.arange(B + 1, dtype=np.int32) * steps)
+    assert max(rel_l2(pooled_np[b], p64[b]) for b in range(B)) <= TOL_POOLED_REL_L2
+    assert np.abs(lse_np - l64).max() <= TOL_LSE_ABS
+    assert_pred_close(preds[-1], oracle.predict(p64, head))
+    sc.close()
