@@ -65,7 +65,7 @@ typedef enum { EGTP_POOL_AVERAGE = 0, EGTP_POOL_MAX = 1, EGTP_POOL_LAST = 2 } eg
 
 /* One prediction head (Section 3.2): x[d] -> relu(w1 x + b1)[d_h] -> w2 . + b2 [n_out]. */
 typedef struct {
-    int32_t d_h;              /* hidden width, > 0 */
+    int32_t d_h;              /* hidden width, 1 .. 16384 */
     int32_t n_out;            /* 1 = scalar length; K > 1 = K-bin head decoded with Eq. 6 (K <= 1024) */
     egtp_dtype wdtype;        /* storage type of w1 and w2 */
     const void *w1;           /* [d_h x d]     device */

@@ -88,7 +88,7 @@ struct Workspace {
     float *lse_new;      // [B]
     float *state_scale;  // [B]
     float *pool_part;    // [units_bound x d]
-    float *act;          // [B x d_h_max]
+    float *act;          // [k splits x B x d_h_max]
     unsigned char *hidden_packed;  // bf16 only: packed copy of this call's hidden states
     unsigned char *w_packed;       // bf16 only, when no persistent packed W_lm was given
     size_t bytes;
@@ -106,7 +106,7 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     w.lse_new = cv.take<float>((size_t)B);
     w.state_scale = cv.take<float>((size_t)B);
     w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
-    w.act = cv.take<float>((size_t)B * (size_t)dh);
+    w.act = cv.take<float>((size_t)head_k_splits(c.d) * (size_t)B * (size_t)dh);
     w.hidden_packed = nullptr;
     w.w_packed = nullptr;
     if (c.dtype == EGTP_BF16) {
@@ -120,7 +120,7 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
 
 egtp_status check_head(const egtp_head &h)
 {
-    if (h.d_h <= 0 || h.n_out <= 0 || h.n_out > 1024)
+    if (h.d_h <= 0 || h.d_h > 16384 || h.n_out <= 0 || h.n_out > 1024)
         return EGTP_ERR_SHAPE;
     if (h.wdtype != EGTP_F32 && h.wdtype != EGTP_BF16)
         return EGTP_ERR_DTYPE;

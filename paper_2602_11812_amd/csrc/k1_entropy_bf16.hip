@@ -372,6 +372,41 @@ __global__ __launch_bounds__(256) void k1_merge_kernel(const float *__restrict__
     entropy[t] = logf(a.S) - a.U * 0.6931471805599453f / a.S;
 }
 
+// The same merge for many ranges per token (small batches split the vocabulary finely): one
+// wave per token, lane l takes ranges l, l+64, ... in order, then a fixed xor tree joins the
+// lanes -- still a fixed order, so bit-reproducible.
+__global__ __launch_bounds__(256) void k1_merge_wide_kernel(const float *__restrict__ part, int nsplit,
+                                                            long T, float *__restrict__ entropy)
+{
+    const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (t >= T)
+        return;
+    const long plane = (long)nsplit * T;
+    Stats a;
+    a.m = NEG_BIG;
+    a.S = 0.f;
+    a.U = 0.f;
+    for (int s = lane; s < nsplit; s += 64) {
+        Stats b;
+        const long idx = (long)s * T + t;
+        b.m = part[idx];
+        b.S = part[plane + idx];
+        b.U = part[2 * plane + idx];
+        a = merge(a, b);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        Stats b;
+        b.m = __shfl_xor(a.m, o);
+        b.S = __shfl_xor(a.S, o);
+        b.U = __shfl_xor(a.U, o);
+        a = merge(a, b);
+    }
+    if (lane == 0)
+        entropy[t] = logf(a.S) - a.U * 0.6931471805599453f / a.S;
+}
+
 // Packs rows of a row-major bf16 matrix src[R x d] into blocks of 256 rows x 32 K-elements in
 // LDS-image order; rows >= R and K >= d are zero.  One workgroup packs 8 consecutive K steps
 // of one row tile: a wave reads 512 contiguous bytes of each of two rows at a time.
@@ -446,6 +481,14 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
 
 hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st)
 {
+    if (nsplit >= 32) {
+        const long wblocks = (T + 3) / 4;
+        if (wblocks <= 0 || wblocks > 0x7fffffffL)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k1_merge_wide_kernel, dim3((unsigned)wblocks), dim3(256), 0, st, part, nsplit, (long)T,
+                           entropy);
+        return hipGetLastError();
+    }
     const long blocks = (T + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffL)
         return hipErrorInvalidValue;

@@ -3,7 +3,10 @@
 //
 // Layer 1 is a small [B x d] . [d x d_h] contraction kept entirely in fp32 (the pooled
 // vector is never re-rounded); it is LDS-tiled, 64 x 64 outputs per workgroup, 4 x 4 per
-// thread.  Layer 2 and the K-bin decode are one wave per sequence.
+// thread, and split along d (blockIdx.z) so that a few hundred workgroups exist even for one
+// small batch; the splits leave partial pre-activations that layer 2 adds in split order
+// (fixed order, bit-reproducible) before bias and ReLU.  Layer 2 and the K-bin decode are one
+// wave per sequence.
 #include "kernels.h"
 
 namespace egtp {
@@ -17,9 +20,8 @@ constexpr int PAD = 4;
 template <bool WBF16>
 __global__ __launch_bounds__(256) void head_layer1_kernel(const float *__restrict__ x,
                                                           const int32_t *__restrict__ slot, int B, int d,
-                                                          int d_h, const void *__restrict__ w1,
-                                                          const float *__restrict__ b1,
-                                                          float *__restrict__ act)
+                                                          int d_h, const void *__restrict__ w1, int kchunk,
+                                                          float *__restrict__ act_part)
 {
     __shared__ float As[TK][TM + PAD];  // As[k][j]
     __shared__ float Bs[TK][TN + PAD];  // Bs[k][sequence]
@@ -43,9 +45,12 @@ __global__ __launch_bounds__(256) void head_layer1_kernel(const float *__restric
         for (int j = 0; j < 4; ++j)
             acc[i][j] = 0.f;
 
-    for (int k0 = 0; k0 < d; k0 += TK) {
+    const int kbeg = blockIdx.z * kchunk;
+    const int kend = min(d, kbeg + kchunk);
+    float *act = act_part + (long)blockIdx.z * B * d_h;
+    for (int k0 = kbeg; k0 < kend; k0 += TK) {
         float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-        if (k0 + lk < d) {
+        if (k0 + lk < kend) {
             if (WBF16) {
                 const uint2 q = *(const uint2 *)((const unsigned short *)w1 + (long)jrow * d + k0 + lk);
                 a.x = __uint_as_float(q.x << 16);
@@ -88,10 +93,8 @@ __global__ __launch_bounds__(256) void head_layer1_kernel(const float *__restric
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int jj = j0 + tx * 4 + i;
-            if (jj < d_h) {
-                const float pre = acc[i][j] + (b1 ? b1[jj] : 0.f);
-                act[(long)s * d_h + jj] = pre > 0.f ? pre : 0.f;
-            }
+            if (jj < d_h)
+                act[(long)s * d_h + jj] = acc[i][j];
         }
     }
 }
@@ -106,7 +109,8 @@ __device__ __forceinline__ float wave_sum(float v)
 
 // one wave per sequence: out[o] = b2[o] + w2[o,:] . act[b,:]; n_out > 1 => Eq. 6
 template <bool WBF16>
-__global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict__ act, int d_h, int n_out,
+__global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict__ act_part, int nks, int B,
+                                                         const float *__restrict__ b1, int d_h, int n_out,
                                                          const void *__restrict__ w2,
                                                          const float *__restrict__ b2,
                                                          const float *__restrict__ centers,
@@ -114,7 +118,16 @@ __global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict
 {
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
-    const float *a = act + (long)b * d_h;
+    // hidden activations: partial sums in split order, then bias and ReLU; kept in LDS
+    extern __shared__ float a[];
+    for (int j = lane; j < d_h; j += 64) {
+        float pre = 0.f;
+        for (int z = 0; z < nks; ++z)
+            pre += act_part[((long)z * B + b) * d_h + j];
+        pre += b1 ? b1[j] : 0.f;
+        a[j] = pre > 0.f ? pre : 0.f;
+    }
+    __syncthreads();
     // online softmax-expectation over the n_out outputs (every lane carries the same values)
     float m = -__builtin_inff(), den = 0.f, num = 0.f, y = 0.f;
     for (int o = 0; o < n_out; ++o) {
@@ -145,21 +158,32 @@ __global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict
 
 }  // namespace
 
+int head_k_splits(int d)
+{
+    int n = (d + 511) / 512;
+    return n < 1 ? 1 : (n > 8 ? 8 : n);
+}
+
 hipError_t head_forward(const HeadArgs &a, hipStream_t st)
 {
     if (a.B <= 0)
         return hipSuccess;
-    const dim3 grid((a.d_h + TM - 1) / TM, (a.B + TN - 1) / TN);
+    const int nks = head_k_splits(a.d);
+    const int kchunk = ((a.d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
+    const dim3 grid((a.d_h + TM - 1) / TM, (a.B + TN - 1) / TN, nks);
+    const size_t lds2 = (size_t)a.d_h * sizeof(float);
+    if (lds2 > 64 * 1024)
+        return hipErrorInvalidValue;
     if (a.wdtype == DT_BF16) {
-        hipLaunchKernelGGL(head_layer1_kernel<true>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h,
-                           a.w1, a.b1, a.act);
-        hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(64), 0, st, a.act, a.d_h, a.n_out, a.w2,
-                           a.b2, a.bin_centers, a.pred);
+        hipLaunchKernelGGL(head_layer1_kernel<true>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h, a.w1,
+                           kchunk, a.act);
+        hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
+                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
     } else {
-        hipLaunchKernelGGL(head_layer1_kernel<false>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h,
-                           a.w1, a.b1, a.act);
-        hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(64), 0, st, a.act, a.d_h, a.n_out, a.w2,
-                           a.b2, a.bin_centers, a.pred);
+        hipLaunchKernelGGL(head_layer1_kernel<false>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h, a.w1,
+                           kchunk, a.act);
+        hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
+                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
     }
     return hipGetLastError();
 }

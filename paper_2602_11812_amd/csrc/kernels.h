@@ -90,9 +90,11 @@ struct HeadArgs {
     const void *w1; const float *b1;
     const void *w2; const float *b2;
     const float *bin_centers; // [n_out] when n_out > 1
-    float *act;               // workspace [B x d_h]
+    float *act;               // workspace [head_k_splits(d) x B x d_h]: partial pre-activations
     float *pred;              // [B]
 };
+// number of partial pre-activation planes layer 1 leaves (it is split along d)
+int head_k_splits(int d);
 hipError_t head_forward(const HeadArgs &a, hipStream_t st);
 
 }  // namespace egtp
