@@ -12,7 +12,7 @@
 //
 // Both operands are read from a PACKED copy: 256 rows x 32 K-elements per block of 16 KiB,
 // stored exactly as the block sits in LDS (16-byte chunks XOR-swizzled by row so that the
-// MFMA fragment reads are conflict-free).  A K step of a tile is then one contiguous
+// MFMA fragment reads are free of bank conflicts).  A K step of a tile is then one contiguous
 // 16 KiB read, which is what HBM and the Infinity Cache want; reading 64-byte row pieces
 // with a row stride of 2d bytes from the row-major matrices stalls the ring on DRAM page
 // misses.  pack_rows_bf16 builds the packed copy (W_lm once, hidden states once per call;
@@ -51,6 +51,12 @@ static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geome
 struct Stats {
     float m, S, U;
 };
+
+// XOR key of a row's four 16-byte chunks inside a packed block (64-byte rows).  A fragment read
+// takes the same logical chunk of consecutive rows; with this key any 16 consecutive rows fall
+// on 16 different 16-byte bank groups of a 256-byte LDS line, and any 8 consecutive rows on 8
+// different groups of a 128-byte line, so the reads are conflict-free either way.
+__host__ __device__ __forceinline__ int swizzle_key(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -182,12 +188,12 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         }
     };
 
-    // ---- fragment read geometry (row r, chunk c sits at r*64 + ((c ^ ((r>>1)&3)) * 16)) ----
+    // ---- fragment read geometry (row r, chunk c sits at r*64 + ((c ^ swizzle_key(r)) * 16)) ----
     const int l31 = lane & 31;
     const int khalf = lane >> 5;
     const unsigned fragA = (unsigned)(wm * 128 + l31) * ROW_BYTES;
     const unsigned fragB = (unsigned)TILE_BYTES + (unsigned)(wn * 128 + l31) * ROW_BYTES;
-    const int swf = (l31 >> 1) & 3;
+    const int swf = swizzle_key(l31);  // row = l31 + a multiple of 32
     const unsigned swz0 = (unsigned)(((0 + khalf) ^ swf) << 4);
     const unsigned swz1 = (unsigned)(((2 + khalf) ^ swf) << 4);
 
@@ -428,7 +434,7 @@ __global__ __launch_bounds__(256) void pack_rows_bf16_kernel(const unsigned char
         uint4 v = make_uint4(0, 0, 0, 0);
         if (row < R && k_elem < d)
             v = *(const uint4 *)(src + (row * d + k_elem) * 2);
-        *(uint4 *)(blk + r * ROW_BYTES + ((chunk ^ ((r >> 1) & 3)) << 4)) = v;
+        *(uint4 *)(blk + r * ROW_BYTES + ((chunk ^ swizzle_key(r)) << 4)) = v;
     }
 }
 
