@@ -21,6 +21,28 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k1_entropy_bf16_serving_hbm_traffic.txt")
+K1_SOURCE = os.path.join(ROOT, "paper_2602_11812_amd", "csrc", "k1_entropy_bf16.hip")
+
+
+def recorded_traffic():
+    """HBM bytes per launch of the fused kernel on the serving workload, from the committed rocprofv3
+    counter summary -- or None when there is none or the kernel source has changed since it was taken."""
+    import hashlib
+    try:
+        kv = {}
+        for line in open(TRAFFIC_FILE):
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                kv[k.strip()] = v.strip()
+        sha = hashlib.sha256(open(K1_SOURCE, "rb").read()).hexdigest()
+        if kv.get("kernel_source_sha256") != sha:
+            return None
+        return float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def bench_plp(args, gpu, wl, np, torch) -> int:
     """PLP decode workload: one step = plp_step over 512 live sequences with one fresh token each
     (fused LM-head + entropy on [512 x d], state fold, remaining-length head).  Reported apart from
@@ -73,6 +95,9 @@ def main() -> int:
     ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode"],
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--oracle-tokens", type=int, default=256, help="tokens of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy before the timed region (reference dispatch for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU; this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -112,6 +137,12 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     gpu.egtp_profile_enable(sc.ctx, True, max(1, min(1024, args.steps)))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -126,6 +157,8 @@ def main() -> int:
     k1_avg_s = float(k1_ms.mean()) * 1e-3
     flops_per_launch = 2.0 * spec.d * spec.V * T          # algorithmic: 2*d*V per token
     achieved = flops_per_launch / k1_avg_s / 1e12
+
+    traffic = recorded_traffic()
 
     cpu = None
     if args.oracle_tokens > 0:
@@ -153,7 +186,8 @@ def main() -> int:
         "pct_bf16_mfma_peak_whole_step": 100.0 * flops_per_launch / (ms_per_step * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": None, "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
+                     "traffic": traffic if args.workload == "serving" else None,
+                     "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
