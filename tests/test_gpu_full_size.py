@@ -130,3 +130,67 @@ def test_plp_decode_full_batch(gpu):
     assert np.abs(lse_np - l64).max() <= TOL_LSE_ABS
     assert_pred_close(preds[-1], oracle.predict(p64, head))
     sc.close()
+
+
+def test_rl_one_to_many_sampling(gpu):
+    # 64 prompts x 16 samples (1024 state slots), d = 5120, V = 151936: EGTP on the prompts, the
+    # state copied to every sample's slot, then two ragged PLP folds of 64 freshly generated
+    # tokens per still-live sample (decode steps 64 and 128), addressed through `slot`.
+    import torch
+    spec = wl.SPECS["rl_prompts"]
+    w = wl.make(spec)
+    td = gpu.to_device
+    d, P, S_PER = spec.d, spec.B, 16
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    off = sc.build_offsets(torch.from_numpy(w.lengths).cuda(), w.T)
+    out = sc.score(td(w.hidden), off)
+    ooff = oracle.offsets_from_lengths(w.lengths)
+    prompt_ent = out["entropy"].cpu().numpy().astype(np.float64)
+
+    pooled = out["pooled"].repeat_interleave(S_PER, dim=0).contiguous()      # slot = prompt * 16 + sample
+    lse = out["lse"].repeat_interleave(S_PER, dim=0).contiguous()
+    before = (pooled.clone(), lse.clone())
+    cont = wl.rl_continuations(spec, S_PER)
+    assert cont.size == P * S_PER
+    chunks = {}                                   # slot -> list of (hidden chunk, GPU entropies)
+    preds = {}
+    for call, s in enumerate((64, 128)):
+        live = np.nonzero(cont >= s)[0].astype(np.int32)
+        assert 0 < live.size < P * S_PER or call == 0
+        hid = wl.draw_hidden(spec, np.random.default_rng([spec.seed, 7, s]), live.size * 64)
+        coff = (np.arange(live.size + 1, dtype=np.int32) * 64)
+        ent = torch.empty(live.size * 64, dtype=torch.float32, device="cuda")
+        pred = sc.step(td(hid), pooled, lse, offsets_new_dev=torch.from_numpy(coff).cuda(), offsets_new_host=coff,
+                       slot_dev=torch.from_numpy(live).cuda(), entropy_out=ent)
+        ent = ent.cpu().numpy().astype(np.float64)
+        pred = pred.cpu().numpy()
+        for i, sl in enumerate(live):
+            chunks.setdefault(int(sl), []).append((hid[i * 64:(i + 1) * 64], ent[i * 64:(i + 1) * 64]))
+            preds[int(sl)] = pred[i]
+        if call == 0:
+            toks = np.random.default_rng(3).choice(live.size * 64, size=16, replace=False)
+            H = oracle.entropy(np.ascontiguousarray(hid[toks]), w.w_lm)
+            assert np.abs(ent[toks] - H).max() <= TOL_ENTROPY_ABS
+    pooled_np, lse_np = pooled.cpu().numpy(), lse.cpu().numpy()
+
+    # slots whose sample ended before step 64 keep the prompt state bit for bit
+    dead = np.nonzero(cont < 64)[0]
+    for sl in dead:
+        assert torch.equal(pooled[sl], before[0][sl]) and lse[sl] == before[1][sl]
+
+    # sampled slots: fp64 pooling over prompt + folded chunks with the GPU's entropies, then the head
+    head = oracle.Head(w.w1, w.w2)
+    pick = np.random.default_rng(5).choice(sorted(chunks), size=10, replace=False)
+    got_pred, want_pooled = [], []
+    for sl in pick:
+        p = sl // S_PER
+        parts = [w.hidden[ooff[p]:ooff[p + 1]]] + [c[0] for c in chunks[sl]]
+        ents = [prompt_ent[ooff[p]:ooff[p + 1]]] + [c[1] for c in chunks[sl]]
+        cat, H = np.concatenate(parts), np.concatenate(ents)
+        _, p64, l64 = oracle.pool(cat, H, [0, cat.shape[0]])
+        assert rel_l2(pooled_np[sl], p64[0]) <= TOL_POOLED_REL_L2
+        assert abs(lse_np[sl] - l64[0]) <= TOL_LSE_ABS
+        want_pooled.append(p64[0])
+        got_pred.append(preds[int(sl)])
+    assert_pred_close(np.asarray(got_pred), oracle.predict(np.stack(want_pooled), head))
+    sc.close()
