@@ -61,9 +61,14 @@ def _load():
         _lib.oracle_pool_ablation.argtypes = [vp, ci, i32, vp, i32, ci, vp]
         _lib.oracle_head.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, ci, vp]
         _lib.oracle_bin_decode.argtypes = [vp, i32, i32, vp, vp, vp]
+        _lib.oracle_soft_label.argtypes = [i32, i32, vp]
+        _lib.oracle_head_loss_grad.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, dbl,
+                                               vp, vp, vp, vp, vp]
+        _lib.oracle_adamw.argtypes = [vp, vp, vp, vp, i64, dbl, dbl, dbl, dbl, dbl, i64]
         for name in ("oracle_offsets", "oracle_seg_ids", "oracle_entropy_from_logits",
                      "oracle_logits", "oracle_entropy", "oracle_pool", "oracle_pool_ablation",
-                     "oracle_head", "oracle_bin_decode"):
+                     "oracle_head", "oracle_bin_decode", "oracle_soft_label", "oracle_head_loss_grad",
+                     "oracle_adamw"):
             getattr(_lib, name).restype = ci
     return _lib
 
@@ -268,3 +273,65 @@ def plp(prompt_hidden: np.ndarray, prompt_offsets, generated: Sequence[np.ndarra
         cat = np.concatenate(rows, axis=0)
         out.append(egtp(cat, offsets_from_lengths(lens), w_lm, head_rem, alpha))
     return out
+
+
+# --------------------------------------------------------------------------- training objective
+def soft_label(i: int, K: int) -> np.ndarray:
+    """Eq. 5: soft label distribution over K bins for a target in bin i (0-based)."""
+    p = np.zeros(K, dtype=np.float64)
+    _check(_load().oracle_soft_label(int(i), int(K), _p(p)), "soft_label")
+    return p
+
+
+@dataclass
+class TrainHead:
+    """fp64 parameters of a K-bin head d -> d_h (ReLU) -> K and its AdamW moments."""
+    w1: np.ndarray
+    b1: np.ndarray
+    w2: np.ndarray
+    b2: np.ndarray
+    centers: np.ndarray
+    m: Optional[list] = None
+    v: Optional[list] = None
+    t: int = 0
+
+    def params(self):
+        return [self.w1, self.b1, self.w2, self.b2]
+
+
+def head_loss_grad(x, bins, y, head: TrainHead, lam: float, weight=None):
+    """Eq. 7 (Eq. 9 via weights): returns (loss3 = [total, CE, MSE], [g_w1, g_b1, g_w2, g_b2])."""
+    x = _c(np.asarray(x, dtype=np.float64))
+    bins = _c(np.asarray(bins, dtype=np.int32))
+    y = _c(np.asarray(y, dtype=np.float64))
+    wgt = None if weight is None else _c(np.asarray(weight, dtype=np.float64))
+    B, d = x.shape
+    d_h, K = head.w1.shape[0], head.w2.shape[0]
+    ps = [_c(np.asarray(a, dtype=np.float64)) for a in (head.w1, head.b1, head.w2, head.b2, head.centers)]
+    loss = np.zeros(3, dtype=np.float64)
+    gs = [np.zeros_like(ps[i]) for i in range(4)]
+    _check(_load().oracle_head_loss_grad(_p(x), _p(bins), _p(y), _p(wgt), B, d, d_h, K, _p(ps[0]), _p(ps[1]),
+                                         _p(ps[2]), _p(ps[3]), _p(ps[4]), float(lam), _p(loss), _p(gs[0]),
+                                         _p(gs[1]), _p(gs[2]), _p(gs[3])), "head_loss_grad")
+    return loss, gs
+
+
+def adamw_step(w, m, v, g, lr, beta1, beta2, eps, weight_decay, t) -> None:
+    """One AdamW step in place on fp64 arrays (contiguous)."""
+    for a in (w, m, v, g):
+        assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    _check(_load().oracle_adamw(_p(w), _p(m), _p(v), _p(g), w.size, float(lr), float(beta1), float(beta2),
+                                float(eps), float(weight_decay), int(t)), "adamw")
+
+
+def train_step(x, bins, y, head: TrainHead, lam=0.95, lr=2e-5, beta1=0.9, beta2=0.999, eps=1e-8,
+               weight_decay=0.01, weight=None):
+    """Loss, gradient and one AdamW update of every head parameter (in place). Returns loss3."""
+    loss, gs = head_loss_grad(x, bins, y, head, lam, weight)
+    if head.m is None:
+        head.m = [np.zeros_like(p) for p in head.params()]
+        head.v = [np.zeros_like(p) for p in head.params()]
+    head.t += 1
+    for p, m, v, g in zip(head.params(), head.m, head.v, gs):
+        adamw_step(p, m, v, g, lr, beta1, beta2, eps, weight_decay, head.t)
+    return loss

@@ -20,6 +20,10 @@
  * vocabulary-duplication invariants, library cross-checks (scipy softmax+entr,
  * logsumexp), mean-pooling and single-token special cases, the merge law,
  * brute force in exact rational arithmetic, and a hand-derived worked example.
+ * The training objective of the head (Eq. 5-7, Eq. 9 as per-sample weights, AdamW)
+ * is pinned by closed forms of the soft label, central finite differences of the
+ * loss for every gradient, torch's autograd and torch.optim.AdamW in fp64 on the
+ * CPU, and the closed form of the first AdamW step.
  * Parity unpinned (stated here and in the design notes): the meaning of a
  * temperature alpha != 1 (Eq. 3 prints no alpha; this file divides H by alpha),
  * and any bin centres for the K-bin decode (the paper never gives them; the
@@ -313,6 +317,139 @@ int oracle_bin_decode(const double *logits, int32_t B, int32_t K, const double *
             y += p * centers[i];
         }
         y_hat[b] = y;
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Training objective of the prediction head on frozen pooled features         */
+/* (Section 3.2, Eq. 5-7; Eq. 9 through per-sample weights).                   */
+/* ------------------------------------------------------------------------- */
+
+/* Eq. 5: soft label over K bins for a target that falls into bin i (0-based):  */
+/* p_j = exp(-|j - i|) / sum_k exp(-|k - i|).                                   */
+int oracle_soft_label(int32_t i, int32_t K, double *p)
+{
+    if (K <= 0 || i < 0 || i >= K || !p)
+        return ORC_BAD_ARG;
+    double Z = 0.0;
+    for (int32_t k = 0; k < K; ++k)
+        Z += exp(-fabs((double)(k - i)));
+    for (int32_t j = 0; j < K; ++j)
+        p[j] = exp(-fabs((double)(j - i))) / Z;
+    return ORC_OK;
+}
+
+/* Eq. 7 with its gradient.  Parameters are fp64 here: w1[d_h x d], b1[d_h], w2[K x d_h],    */
+/* b2[K]; x[B x d] pooled features; bin[B] the target's bin, y[B] the target length;          */
+/* weight[B] per-sample weights (NULL = 1/B each; Eq. 9 averages a sequence's steps by        */
+/* giving each of its T steps weight 1/(N T)); c[K] bin centres.                              */
+/*   loss = sum_b weight_b ( lambda * CE_b + (1 - lambda) * (y_b - yhat_b)^2 ),               */
+/*   CE_b = - sum_j p_bj log phat_bj,  phat_b = softmax(z_b),  yhat_b = sum_j phat_bj c_j,     */
+/*   z_b = w2 relu(w1 x_b + b1) + b2.                                                         */
+/* loss3 = {total, weighted CE part, weighted MSE part} (each before the lambda factors for   */
+/* the two parts).  Gradients may each be NULL.                                               */
+int oracle_head_loss_grad(const double *x, const int32_t *bin, const double *y, const double *weight,
+                          int32_t B, int32_t d, int32_t d_h, int32_t K, const double *w1,
+                          const double *b1, const double *w2, const double *b2, const double *c,
+                          double lambda, double *loss3, double *g_w1, double *g_b1, double *g_w2,
+                          double *g_b2)
+{
+    if (B <= 0 || d <= 0 || d_h <= 0 || K <= 0 || !x || !bin || !y || !w1 || !b1 || !w2 || !b2 || !c || !loss3)
+        return ORC_BAD_ARG;
+    if (g_w1) memset(g_w1, 0, sizeof(double) * (size_t)d_h * d);
+    if (g_b1) memset(g_b1, 0, sizeof(double) * (size_t)d_h);
+    if (g_w2) memset(g_w2, 0, sizeof(double) * (size_t)K * d_h);
+    if (g_b2) memset(g_b2, 0, sizeof(double) * (size_t)K);
+    double *a = (double *)malloc(sizeof(double) * (size_t)d_h);
+    double *da = (double *)malloc(sizeof(double) * (size_t)d_h);
+    double *z = (double *)malloc(sizeof(double) * (size_t)K);
+    double *ph = (double *)malloc(sizeof(double) * (size_t)K);
+    double *p = (double *)malloc(sizeof(double) * (size_t)K);
+    double *dz = (double *)malloc(sizeof(double) * (size_t)K);
+    if (!a || !da || !z || !ph || !p || !dz) {
+        free(a); free(da); free(z); free(ph); free(p); free(dz);
+        return ORC_NO_MEM;
+    }
+    double ce_sum = 0.0, mse_sum = 0.0;
+    int rc = ORC_OK;
+    for (int32_t b = 0; b < B && rc == ORC_OK; ++b) {
+        const double wb = weight ? weight[b] : 1.0 / (double)B;
+        const double *xb = x + (int64_t)b * d;
+        for (int32_t j = 0; j < d_h; ++j) {
+            double pre = b1[j];
+            for (int32_t k = 0; k < d; ++k)
+                pre += w1[(int64_t)j * d + k] * xb[k];
+            a[j] = pre > 0.0 ? pre : 0.0;
+        }
+        double m = -INFINITY;
+        for (int32_t o = 0; o < K; ++o) {
+            double s = b2[o];
+            for (int32_t j = 0; j < d_h; ++j)
+                s += w2[(int64_t)o * d_h + j] * a[j];
+            z[o] = s;
+            if (s > m) m = s;
+        }
+        double S = 0.0;
+        for (int32_t o = 0; o < K; ++o)
+            S += exp(z[o] - m);
+        double yhat = 0.0;
+        for (int32_t o = 0; o < K; ++o) {
+            ph[o] = exp(z[o] - m) / S;
+            yhat += ph[o] * c[o];
+        }
+        rc = oracle_soft_label(bin[b], K, p);
+        if (rc != ORC_OK)
+            break;
+        double ce = 0.0;
+        for (int32_t o = 0; o < K; ++o)
+            ce -= p[o] * ((z[o] - m) - log(S));
+        const double err = yhat - y[b];
+        ce_sum += wb * ce;
+        mse_sum += wb * err * err;
+        /* d loss / d z_o = wb ( lambda (phat_o - p_o) + (1-lambda) 2 err phat_o (c_o - yhat) ) */
+        for (int32_t o = 0; o < K; ++o)
+            dz[o] = wb * (lambda * (ph[o] - p[o]) + (1.0 - lambda) * 2.0 * err * ph[o] * (c[o] - yhat));
+        for (int32_t j = 0; j < d_h; ++j) {
+            double s = 0.0;
+            for (int32_t o = 0; o < K; ++o)
+                s += dz[o] * w2[(int64_t)o * d_h + j];
+            da[j] = a[j] > 0.0 ? s : 0.0;
+        }
+        for (int32_t o = 0; o < K; ++o) {
+            if (g_b2) g_b2[o] += dz[o];
+            if (g_w2)
+                for (int32_t j = 0; j < d_h; ++j)
+                    g_w2[(int64_t)o * d_h + j] += dz[o] * a[j];
+        }
+        for (int32_t j = 0; j < d_h; ++j) {
+            if (g_b1) g_b1[j] += da[j];
+            if (g_w1 && da[j] != 0.0)
+                for (int32_t k = 0; k < d; ++k)
+                    g_w1[(int64_t)j * d + k] += da[j] * xb[k];
+        }
+    }
+    loss3[0] = lambda * ce_sum + (1.0 - lambda) * mse_sum;
+    loss3[1] = ce_sum;
+    loss3[2] = mse_sum;
+    free(a); free(da); free(z); free(ph); free(p); free(dz);
+    return rc;
+}
+
+/* AdamW (decoupled weight decay), one step t >= 1 on n parameters:                         */
+/*   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  mhat = m/(1-b1^t);  vhat = v/(1-b2^t);    */
+/*   w = w - lr * wd * w - lr * mhat / (sqrt(vhat) + eps).                                   */
+int oracle_adamw(double *w, double *m, double *v, const double *g, int64_t n, double lr, double beta1,
+                 double beta2, double eps, double weight_decay, int64_t t)
+{
+    if (n < 0 || t < 1 || (n > 0 && (!w || !m || !v || !g)))
+        return ORC_BAD_ARG;
+    const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        m[i] = beta1 * m[i] + (1.0 - beta1) * g[i];
+        v[i] = beta2 * v[i] + (1.0 - beta2) * g[i] * g[i];
+        const double mhat = m[i] / c1, vhat = v[i] / c2;
+        w[i] = w[i] - lr * weight_decay * w[i] - lr * mhat / (sqrt(vhat) + eps);
     }
     return ORC_OK;
 }
