@@ -55,7 +55,8 @@ typedef enum {
     EGTP_ERR_WORKSPACE = 5, /* workspace NULL, misaligned (256 B) or too small */
     EGTP_ERR_ARCH = 6,      /* current device is not gfx950 */
     EGTP_ERR_HIP = 7,       /* a HIP call failed; see egtp_last_hip_error */
-    EGTP_ERR_ALPHA = 8      /* temperature not a finite number > 0 */
+    EGTP_ERR_ALPHA = 8,     /* temperature not a finite number > 0 */
+    EGTP_ERR_HYPER = 9      /* a training hyper-parameter is outside its range */
 } egtp_status;
 
 typedef enum { EGTP_F32 = 0, EGTP_BF16 = 1 } egtp_dtype;
@@ -157,6 +158,52 @@ egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t 
                                const int32_t *offsets_host, int32_t B, int64_t T,
                                egtp_pool_kind kind, void *workspace, size_t workspace_bytes,
                                float *pooled_out, float *pred_out, void *stream);
+
+/* Training of a K-bin head on frozen features (Section 3.2, 3.3; optimiser settings of the
+ * experimental setup).  State of one head: fp32 parameters and their AdamW moments, all device
+ * memory owned by the caller, all updated in place by egtp_head_train_step.  After training the
+ * same w1/b1/w2/b2/bin_centers serve as an egtp_head with wdtype = EGTP_F32 and n_out = K. */
+typedef struct {
+    int32_t d;                /* feature size (multiple of 4) */
+    int32_t d_h;              /* hidden width, 1 .. 16384 */
+    int32_t K;                /* bins, 1 .. 1024 */
+    float *w1, *b1;           /* [d_h x d], [d_h] */
+    float *w2, *b2;           /* [K x d_h], [K] */
+    float *m_w1, *v_w1;       /* first / second moment of each parameter, same shapes; zeros before */
+    float *m_b1, *v_b1;       /* the first step */
+    float *m_w2, *v_w2;
+    float *m_b2, *v_b2;
+    const float *bin_centers; /* [K], the c_i of Eq. 6 */
+    float lambda;             /* weight of the cross-entropy term in Eq. 7, 0 .. 1 */
+    float lr, beta1, beta2, eps, weight_decay; /* AdamW; lr >= 0, 0 <= beta < 1, eps > 0, decay >= 0 */
+    int64_t t;                /* number of this step, 1 for the first (bias correction) */
+    float *g_w1, *g_b1;       /* optional: receive the gradient of each parameter (NULL = not wanted) */
+    float *g_w2, *g_b2;
+} egtp_head_train;
+
+/* Workspace bytes of one egtp_head_train_step with B samples; 0 if an argument is invalid. */
+size_t egtp_head_train_workspace_bytes(int32_t B, int32_t d, int32_t d_h, int32_t K);
+
+/* One optimisation step on B samples (x_b, bin_b, y_b):
+ *   logits z_b = w2 relu(w1 x_b + b1) + b2,  phat_b = softmax(z_b),  yhat_b = sum_j phat_bj c_j  (Eq. 6)
+ *   soft label p_bj = exp(-|j - bin_b|) / sum_k exp(-|k - bin_b|)                               (Eq. 5)
+ *   loss = sum_b weight_b ( lambda CE(p_b, phat_b) + (1 - lambda) (y_b - yhat_b)^2 )             (Eq. 7)
+ *   weight_b = 1/B, or, for PLP samples, 1 / (n_seqs * steps_per_seq[b]): the average over a
+ *   sequence's decode steps, then over sequences                                               (Eq. 9)
+ * followed by the gradient with respect to the four head parameters and one AdamW update
+ *   m = beta1 m + (1-beta1) g,  v = beta2 v + (1-beta2) g^2,
+ *   w = w - lr weight_decay w - lr (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps).
+ *   x              [B x d] fp32 device: pooled vectors (egtp_score's pooled_out, a PLP state)
+ *   bin            [B] int32 device: bin of the target, 0-based; values outside 0..K-1 are clamped.
+ *                  The paper does not define the bin edges: the caller does the binning.
+ *   y              [B] fp32 device: target length, in the unit of bin_centers
+ *   steps_per_seq  [B] int32 device or NULL: for sample b, the number of decode steps (>= 1)
+ *                  its sequence contributes to this batch; n_seqs = sequences in the batch
+ *   loss_out       [3] fp32 device: the loss above, its CE sum and its MSE sum (before lambda)
+ * Everything is enqueued on `stream`; nothing is allocated; fixed summation orders. */
+egtp_status egtp_head_train_step(const egtp_head_train *head, const float *x, const int32_t *bin,
+                                 const float *y, const int32_t *steps_per_seq, int32_t n_seqs, int32_t B,
+                                 void *workspace, size_t workspace_bytes, float *loss_out, void *stream);
 
 /* Measurement aid: when enabled, every egtp_score / plp_step call brackets its fused LM-head +
  * entropy kernel (the Eq. 2 contraction, where nearly all of the work is) with a pair of HIP

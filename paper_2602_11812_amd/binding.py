@@ -23,7 +23,8 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
-           "egtp_profile_enable", "egtp_profile_read", "egtp_packed_w_lm_bytes", "egtp_pack_w_lm")
+           "egtp_profile_enable", "egtp_profile_read", "egtp_packed_w_lm_bytes", "egtp_pack_w_lm",
+           "egtp_head_train_workspace_bytes", "egtp_head_train_step")
 
 
 class egtp_head(Structure):
@@ -35,6 +36,17 @@ class egtp_head(Structure):
 class egtp_config(Structure):
     _fields_ = [("d", c_int32), ("vocab", c_int32), ("dtype", c_int), ("w_lm", c_void_p),
                 ("alpha", c_float), ("head_len", egtp_head), ("head_rem", egtp_head)]
+
+
+class egtp_head_train(Structure):
+    _fields_ = [("d", c_int32), ("d_h", c_int32), ("K", c_int32),
+                ("w1", c_void_p), ("b1", c_void_p), ("w2", c_void_p), ("b2", c_void_p),
+                ("m_w1", c_void_p), ("v_w1", c_void_p), ("m_b1", c_void_p), ("v_b1", c_void_p),
+                ("m_w2", c_void_p), ("v_w2", c_void_p), ("m_b2", c_void_p), ("v_b2", c_void_p),
+                ("bin_centers", c_void_p),
+                ("lambda_", c_float), ("lr", c_float), ("beta1", c_float), ("beta2", c_float),
+                ("eps", c_float), ("weight_decay", c_float), ("t", c_int64),
+                ("g_w1", c_void_p), ("g_b1", c_void_p), ("g_w2", c_void_p), ("g_b2", c_void_p)]
 
 
 class EgtpError(RuntimeError):
@@ -82,6 +94,10 @@ def load_library() -> ctypes.CDLL:
     lib.egtp_profile_enable.restype = c_int
     lib.egtp_profile_read.argtypes = [vp, vp, c_int]
     lib.egtp_profile_read.restype = c_int
+    lib.egtp_head_train_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.egtp_head_train_workspace_bytes.restype = c_size_t
+    lib.egtp_head_train_step.argtypes = [POINTER(egtp_head_train), vp, vp, vp, vp, i32, i32, vp, c_size_t, vp, vp]
+    lib.egtp_head_train_step.restype = c_int
     _lib = lib
     return lib
 
@@ -227,7 +243,71 @@ def egtp_profile_read(ctx, cap: int = 1024) -> np.ndarray:
     return buf[:n].copy()
 
 
+def egtp_head_train_workspace_bytes(B: int, d: int, d_h: int, K: int) -> int:
+    return int(load_library().egtp_head_train_workspace_bytes(int(B), int(d), int(d_h), int(K)))
+
+
+def egtp_head_train_step(head: egtp_head_train, x, bin, y, steps_per_seq, n_seqs, B, workspace, loss_out,
+                         stream=None) -> None:
+    st = load_library().egtp_head_train_step(byref(head), _dev(x), _dev(bin), _dev(y), _dev(steps_per_seq),
+                                             int(n_seqs), int(B), _dev(workspace),
+                                             workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                             _dev(loss_out), _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_head_train_step")
+
+
 # --------------------------------------------------------------------------- convenience (memory only)
+class HeadTrainer:
+    """Owns the fp32 parameters, AdamW moments and workspace of one K-bin head.  No arithmetic here."""
+
+    def __init__(self, w1, b1, w2, b2, bin_centers, lam=0.95, lr=2e-5, beta1=0.9, beta2=0.999, eps=1e-8,
+                 weight_decay=0.01, keep_grads=False):
+        self.params = dict(w1=w1, b1=b1, w2=w2, b2=b2)
+        for p in self.params.values():
+            if p.dtype != torch.float32:
+                raise TypeError("training keeps fp32 parameters")
+        self.centers = bin_centers
+        self.m = {k: torch.zeros_like(p) for k, p in self.params.items()}
+        self.v = {k: torch.zeros_like(p) for k, p in self.params.items()}
+        self.grads = {k: torch.zeros_like(p) for k, p in self.params.items()} if keep_grads else None
+        self.hyper = dict(lam=lam, lr=lr, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay)
+        self.t = 0
+        self.d_h, self.d = w1.shape
+        self.K = w2.shape[0]
+        self.loss = torch.zeros(3, dtype=torch.float32, device="cuda")
+        self._ws = None
+
+    def _struct(self) -> egtp_head_train:
+        h = egtp_head_train()
+        h.d, h.d_h, h.K = self.d, self.d_h, self.K
+        for k, p in self.params.items():
+            setattr(h, k, _dev(p))
+            setattr(h, "m_" + k, _dev(self.m[k]))
+            setattr(h, "v_" + k, _dev(self.v[k]))
+            setattr(h, "g_" + k, _dev(self.grads[k]) if self.grads else None)
+        h.bin_centers = _dev(self.centers)
+        hp = self.hyper
+        h.lambda_, h.lr, h.beta1, h.beta2 = hp["lam"], hp["lr"], hp["beta1"], hp["beta2"]
+        h.eps, h.weight_decay, h.t = hp["eps"], hp["weight_decay"], self.t
+        return h
+
+    def step(self, x, bins, y, steps_per_seq=None, n_seqs=0) -> torch.Tensor:
+        """One optimisation step; returns the device tensor [loss, CE, MSE] (valid after a sync)."""
+        B = x.shape[0]
+        need = egtp_head_train_workspace_bytes(B, self.d, self.d_h, self.K)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        self.t += 1
+        egtp_head_train_step(self._struct(), x, bins, y, steps_per_seq, n_seqs, B, self._ws, self.loss)
+        return self.loss
+
+    def as_head(self) -> egtp_head:
+        """The trained parameters as a scoring head (fp32 storage, n_out = K)."""
+        p = self.params
+        return make_head(p["w1"], p["w2"], p["b1"], p["b2"], self.centers)
+
+
 class Scorer:
     """Owns a context plus torch-allocated outputs and workspace.  No arithmetic here."""
 

@@ -241,6 +241,7 @@ const char *egtp_status_string(egtp_status s)
     case EGTP_ERR_ARCH: return "current device is not gfx950";
     case EGTP_ERR_HIP: return "HIP call failed";
     case EGTP_ERR_ALPHA: return "temperature must be finite and > 0";
+    case EGTP_ERR_HYPER: return "training hyper-parameter out of range";
     }
     return "unknown status";
 }
@@ -517,6 +518,107 @@ egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t 
         return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
     }
     return EGTP_OK;
+}
+
+// ---- head training ----------------------------------------------------------------------------
+namespace {
+
+struct TrainWorkspace {
+    float *act_part, *act, *dact, *dz, *loss_part;
+    size_t bytes;
+};
+
+TrainWorkspace carve_train(void *base, int32_t B, int32_t d, int32_t d_h, int32_t K)
+{
+    Carver cv(base);
+    TrainWorkspace w;
+    w.act_part = cv.take<float>((size_t)head_k_splits(d) * (size_t)B * (size_t)d_h);
+    w.act = cv.take<float>((size_t)B * (size_t)d_h);
+    w.dact = cv.take<float>((size_t)B * (size_t)d_h);
+    w.dz = cv.take<float>((size_t)B * (size_t)K);
+    w.loss_part = cv.take<float>((size_t)B * 2);
+    w.bytes = cv.off;
+    return w;
+}
+
+bool train_shape_ok(int32_t B, int32_t d, int32_t d_h, int32_t K)
+{
+    return B >= 0 && d > 0 && d % 4 == 0 && d_h > 0 && d_h <= 16384 && K > 0 && K <= 1024;
+}
+
+}  // namespace
+
+size_t egtp_head_train_workspace_bytes(int32_t B, int32_t d, int32_t d_h, int32_t K)
+{
+    if (!train_shape_ok(B, d, d_h, K))
+        return 0;
+    return carve_train(nullptr, B, d, d_h, K).bytes;
+}
+
+egtp_status egtp_head_train_step(const egtp_head_train *h, const float *x, const int32_t *bin, const float *y,
+                                 const int32_t *steps_per_seq, int32_t n_seqs, int32_t B, void *workspace,
+                                 size_t workspace_bytes, float *loss_out, void *stream)
+{
+    if (!h)
+        return EGTP_ERR_NULL;
+    if (!train_shape_ok(B, h->d, h->d_h, h->K))
+        return EGTP_ERR_SHAPE;
+    if (!h->w1 || !h->b1 || !h->w2 || !h->b2 || !h->m_w1 || !h->v_w1 || !h->m_b1 || !h->v_b1 || !h->m_w2 ||
+        !h->v_w2 || !h->m_b2 || !h->v_b2 || !h->bin_centers)
+        return EGTP_ERR_NULL;
+    if (!(h->lambda >= 0.0f && h->lambda <= 1.0f) || !(h->lr >= 0.0f) || !isfinite(h->lr) ||
+        !(h->beta1 >= 0.0f && h->beta1 < 1.0f) || !(h->beta2 >= 0.0f && h->beta2 < 1.0f) || !(h->eps > 0.0f) ||
+        !isfinite(h->eps) || !(h->weight_decay >= 0.0f) || !isfinite(h->weight_decay) || h->t < 1)
+        return EGTP_ERR_HYPER;
+    if (B == 0)
+        return EGTP_OK;
+    if (!x || !bin || !y || !loss_out)
+        return EGTP_ERR_NULL;
+    if (steps_per_seq && n_seqs <= 0)
+        return EGTP_ERR_SHAPE;
+    if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 ||
+        workspace_bytes < egtp_head_train_workspace_bytes(B, h->d, h->d_h, h->K))
+        return EGTP_ERR_WORKSPACE;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+        strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return EGTP_ERR_ARCH;
+
+    const TrainWorkspace w = carve_train(workspace, B, h->d, h->d_h, h->K);
+    TrainArgs a;
+    a.x = x;
+    a.bin = bin;
+    a.y = y;
+    a.steps = steps_per_seq;
+    a.n_seqs = n_seqs;
+    a.B = B;
+    a.d = h->d;
+    a.d_h = h->d_h;
+    a.K = h->K;
+    a.w1 = h->w1, a.b1 = h->b1, a.w2 = h->w2, a.b2 = h->b2;
+    a.m_w1 = h->m_w1, a.v_w1 = h->v_w1, a.m_b1 = h->m_b1, a.v_b1 = h->v_b1;
+    a.m_w2 = h->m_w2, a.v_w2 = h->v_w2, a.m_b2 = h->m_b2, a.v_b2 = h->v_b2;
+    a.centers = h->bin_centers;
+    a.lambda = h->lambda;
+    a.lr = h->lr;
+    a.beta1 = h->beta1;
+    a.beta2 = h->beta2;
+    a.eps = h->eps;
+    a.weight_decay = h->weight_decay;
+    // scalar factors of the update, formed once in double
+    a.omb1 = (float)(1.0 - (double)h->beta1);
+    a.omb2 = (float)(1.0 - (double)h->beta2);
+    a.corr1 = (float)(1.0 - pow((double)h->beta1, (double)h->t));
+    a.corr2 = (float)(1.0 - pow((double)h->beta2, (double)h->t));
+    a.g_w1 = h->g_w1, a.g_b1 = h->g_b1, a.g_w2 = h->g_w2, a.g_b2 = h->g_b2;
+    a.loss = loss_out;
+    a.act_part = w.act_part;
+    a.act = w.act;
+    a.dact = w.dact;
+    a.dz = w.dz;
+    a.loss_part = w.loss_part;
+    return head_train_step(a, (hipStream_t)stream) == hipSuccess ? EGTP_OK : EGTP_ERR_HIP;
 }
 
 }  // extern "C"

@@ -164,27 +164,40 @@ int head_k_splits(int d)
     return n < 1 ? 1 : (n > 8 ? 8 : n);
 }
 
+hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, int d_h, const void *w1,
+                       int wdtype, float *act_part, hipStream_t st)
+{
+    if (B <= 0)
+        return hipSuccess;
+    const int nks = head_k_splits(d);
+    const int kchunk = ((d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
+    const dim3 grid((d_h + TM - 1) / TM, (B + TN - 1) / TN, nks);
+    if (wdtype == DT_BF16)
+        hipLaunchKernelGGL(head_layer1_kernel<true>, grid, dim3(256), 0, st, x, slot, B, d, d_h, w1, kchunk,
+                           act_part);
+    else
+        hipLaunchKernelGGL(head_layer1_kernel<false>, grid, dim3(256), 0, st, x, slot, B, d, d_h, w1, kchunk,
+                           act_part);
+    return hipGetLastError();
+}
+
 hipError_t head_forward(const HeadArgs &a, hipStream_t st)
 {
     if (a.B <= 0)
         return hipSuccess;
     const int nks = head_k_splits(a.d);
-    const int kchunk = ((a.d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
-    const dim3 grid((a.d_h + TM - 1) / TM, (a.B + TN - 1) / TN, nks);
     const size_t lds2 = (size_t)a.d_h * sizeof(float);
     if (lds2 > 64 * 1024)
         return hipErrorInvalidValue;
-    if (a.wdtype == DT_BF16) {
-        hipLaunchKernelGGL(head_layer1_kernel<true>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h, a.w1,
-                           kchunk, a.act);
+    hipError_t e = head_layer1(a.x, a.slot, a.B, a.d, a.d_h, a.w1, a.wdtype, a.act, st);
+    if (e != hipSuccess)
+        return e;
+    if (a.wdtype == DT_BF16)
         hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
                            a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
-    } else {
-        hipLaunchKernelGGL(head_layer1_kernel<false>, grid, dim3(256), 0, st, a.x, a.slot, a.B, a.d, a.d_h, a.w1,
-                           kchunk, a.act);
+    else
         hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
                            a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
-    }
     return hipGetLastError();
 }
 

@@ -96,5 +96,34 @@ struct HeadArgs {
 // number of partial pre-activation planes layer 1 leaves (it is split along d)
 int head_k_splits(int d);
 hipError_t head_forward(const HeadArgs &a, hipStream_t st);
+// layer 1 alone: partial pre-activations act_part[head_k_splits(d) x B x d_h] (no bias, no ReLU)
+hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, int d_h, const void *w1,
+                       int wdtype, float *act_part, hipStream_t st);
+
+// One training step of a K-bin head on frozen features (Eq. 5, 7, 9 + AdamW), fp32 parameters.
+struct TrainArgs {
+    const float *x;            // [B x d] features
+    const int32_t *bin;        // [B] target bin
+    const float *y;            // [B] target length
+    const int32_t *steps;      // [B] decode steps of the sample's sequence (Eq. 9), or NULL
+    int32_t n_seqs;            // sequences in the batch when steps != NULL
+    int32_t B;
+    int d, d_h, K;
+    float *w1, *b1, *w2, *b2;  // parameters, updated in place
+    float *m_w1, *v_w1, *m_b1, *v_b1, *m_w2, *v_w2, *m_b2, *v_b2;  // AdamW moments
+    const float *centers;      // [K]
+    float lambda, lr, beta1, beta2, eps, weight_decay;
+    float omb1, omb2;          // 1 - beta1, 1 - beta2 (rounded once from double)
+    float corr1, corr2;        // 1 - beta1^t, 1 - beta2^t
+    float *g_w1, *g_b1, *g_w2, *g_b2;  // optional copies of the gradients
+    float *loss;               // [3] total, CE part, MSE part
+    // workspace
+    float *act_part;           // [head_k_splits(d) x B x d_h]
+    float *act;                // [B x d_h]
+    float *dact;               // [B x d_h]
+    float *dz;                 // [B x K]
+    float *loss_part;          // [B x 2]
+};
+hipError_t head_train_step(const TrainArgs &a, hipStream_t st);
 
 }  // namespace egtp

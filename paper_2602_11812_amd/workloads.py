@@ -156,3 +156,56 @@ def rl_continuations(spec: Spec, samples_per_prompt: int = 16, mu: float = 7.0,
     rng = np.random.default_rng([spec.seed, 1 << 20])
     raw = np.exp(rng.normal(mu, sigma, size=spec.B * samples_per_prompt))
     return np.clip(np.rint(raw), lo, hi).astype(np.int32)
+
+
+# --------------------------------------------------------------------------- head training data
+@dataclass
+class TrainSet:
+    """Synthetic (feature, length) pairs and an initial K-bin head, all fp32.
+
+    Stands in for pooled vectors of a frozen model paired with observed generation lengths:
+    features are Gaussian, the length is log-normal around a fixed random direction of the
+    feature plus noise (long-tailed, clipped to [1, max_len]).  Bins are ``K`` equal-width
+    intervals of [0, max_len] with their midpoints as centres -- the paper leaves the bin edges
+    open, so the binning is part of the input recipe, not of the method.
+    """
+    x: np.ndarray          # [B x d] fp32
+    y: np.ndarray          # [B] fp32 target length (remaining length for PLP samples)
+    bins: np.ndarray       # [B] int32
+    centers: np.ndarray    # [K] fp32
+    w1: np.ndarray         # [d_h x d]
+    b1: np.ndarray         # [d_h]
+    w2: np.ndarray         # [K x d_h]
+    b2: np.ndarray         # [K]
+    steps: Optional[np.ndarray] = None   # [B] int32: decode steps of the sample's sequence (PLP)
+    n_seqs: int = 0
+
+
+def make_train(seed: int, B: int, d: int, d_h: int, K: int, max_len: float = 2048.0,
+               plp_seqs: int = 0) -> TrainSet:
+    """Draw order: direction -> features -> noise -> W1 -> b1 -> W2 -> b2 [-> steps per sequence].
+
+    plp_seqs > 0: the B samples are decode steps of ``plp_seqs`` sequences (every sequence gets
+    at least one, the rest are dealt at random); ``steps[b]`` is how many its sequence holds."""
+    rng = np.random.default_rng([seed, 1 << 21])
+    u = rng.standard_normal(d).astype(np.float32) / np.float32(np.sqrt(d))
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    noise = rng.standard_normal(B).astype(np.float32)
+    y = np.exp(np.float32(5.5) + np.float32(0.8) * (x @ u) + np.float32(0.3) * noise)
+    y = np.clip(y, 1.0, max_len - 1.0).astype(np.float32)
+    width = np.float32(max_len / K)
+    bins = np.minimum((y / width).astype(np.int32), K - 1).astype(np.int32)
+    centers = ((np.arange(K, dtype=np.float32) + np.float32(0.5)) * width).astype(np.float32)
+    w1 = (rng.standard_normal((d_h, d)) / np.sqrt(d)).astype(np.float32)
+    b1 = (0.1 * rng.standard_normal(d_h)).astype(np.float32)
+    w2 = (rng.standard_normal((K, d_h)) / np.sqrt(d_h)).astype(np.float32)
+    b2 = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    ts = TrainSet(x, y, bins, centers, w1, b1, w2, b2)
+    if plp_seqs > 0:
+        assert plp_seqs <= B
+        owner = np.concatenate([np.arange(plp_seqs), rng.integers(0, plp_seqs, size=B - plp_seqs)])
+        owner = rng.permutation(owner)
+        counts = np.bincount(owner, minlength=plp_seqs)
+        ts.steps = counts[owner].astype(np.int32)
+        ts.n_seqs = plp_seqs
+    return ts

@@ -1,0 +1,259 @@
+"""GPU parity of the head's training step (Eq. 5, 7, 9 + AdamW) against the fp64 oracle.
+
+Bars (derived from the arithmetic: the GPU path keeps fp32 parameters, moments and sums):
+  * loss terms and gradients: relative L2 <= 2e-5 per tensor;
+  * moments after s steps: m relative L2 <= 5e-5, v <= 1e-4 (linear / quadratic in the gradients);
+  * parameters: per element  |w_gpu - w_orc| <= sum over steps of (lr * u_tol + 2e-7 |w|), where
+    the update u = mhat / (sqrt(vhat) + eps) of a step has the sensitivity-aware tolerance
+        u_tol = min(4, 2 dg / (sqrt(vhat) + eps)) + 1e-4,   dg = max over steps so far of
+        2e-5 |g| + 2e-6 rms(g):
+    Adam divides by the gradient's own magnitude, so an element whose gradient is at the fp32
+    noise floor has an update that fp32 cannot determine; everywhere else the bar is ~1e-4 lr.
+    The tests also require that bar to be tight (< 1% of lr) for at least 99% of the elements
+    and that the step moved the parameters by about lr, so a missing update cannot pass.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import assert_pred_close, rel_l2
+from paper_2602_11812_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("w1", "b1", "w2", "b2")
+HYPER = dict(lam=0.95, lr=2e-5, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2602_11812_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load_library()
+    return binding
+
+
+def _trainer(gpu, ts, keep_grads=True, **hyper):
+    td = gpu.to_device
+    hp = dict(HYPER, **hyper)
+    return gpu.HeadTrainer(td(ts.w1), td(ts.b1), td(ts.w2), td(ts.b2), td(ts.centers), keep_grads=keep_grads, **hp)
+
+
+def _oracle_head(ts):
+    f = lambda a: np.array(a, dtype=np.float64)
+    return oracle.TrainHead(f(ts.w1), f(ts.b1), f(ts.w2), f(ts.b2), f(ts.centers))
+
+
+def _weights(ts):
+    return None if ts.steps is None else 1.0 / (ts.n_seqs * ts.steps.astype(np.float64))
+
+
+def _gpu_step(gpu, tr, ts, rows=None):
+    td = gpu.to_device
+    sl = slice(None) if rows is None else rows
+    steps = None if ts.steps is None else td(np.ascontiguousarray(ts.steps[sl]))
+    loss = tr.step(td(np.ascontiguousarray(ts.x[sl])), td(np.ascontiguousarray(ts.bins[sl])),
+                   td(np.ascontiguousarray(ts.y[sl])), steps, ts.n_seqs)
+    return loss.cpu().numpy().astype(np.float64)
+
+
+class _Bar:
+    """Running per-element bar of the module docstring: every step adds lr * u_tol + 2e-7 |w|, with
+    u_tol from the largest gradient error so far and the oracle's second moment at that step."""
+
+    def __init__(self, params):
+        self.dg = [np.zeros_like(p) for p in params]
+        self.tol = [np.zeros_like(p) for p in params]
+        self.seen = [np.zeros(p.shape, dtype=bool) for p in params]
+
+    def add_step(self, oh, gs, hp, s):
+        tight = []
+        for i, g in enumerate(gs):
+            g_rms = float(np.sqrt(np.mean(np.square(g))))
+            self.dg[i] = np.maximum(self.dg[i], 2e-5 * np.abs(g) + 2e-6 * g_rms)
+            self.seen[i] |= g != 0.0
+            vhat = oh.v[i] / (1.0 - hp["beta2"] ** s)
+            u_tol = np.minimum(4.0, 2.0 * self.dg[i] / (np.sqrt(vhat) + hp["eps"])) + 1e-4
+            u_tol[~self.seen[i]] = 1e-4     # exact zeros so far (dead units) are exact on both sides
+            self.tol[i] += hp["lr"] * u_tol + 2e-7 * np.abs(oh.params()[i])
+            tight.append(float(np.mean(u_tol < 1e-2)))
+        return tight
+
+
+def _check_params(tr, oh, bar, tight, gs, hp, w_before):
+    for i, n in enumerate(NAMES):
+        got = tr.params[n].cpu().numpy().astype(np.float64)
+        want = oh.params()[i]
+        bad = np.abs(got - want) > bar.tol[i]
+        assert not bad.any(), f"{n}: {bad.sum()} elements off, worst {np.abs(got - want).max()}"
+        assert tight[i] >= 0.99, f"{n}: bar is tight for only {tight[i]:.4f} of the elements"
+        assert rel_l2(tr.m[n].cpu().numpy(), oh.m[i]) <= 5e-5
+        assert rel_l2(tr.v[n].cpu().numpy(), oh.v[i]) <= 1e-4
+        moved = np.abs(got - w_before[i])
+        live = np.abs(gs[i]) > 1e-3 * np.sqrt(np.mean(np.square(gs[i])))
+        assert np.median(moved[live]) >= 0.3 * hp["lr"], f"{n} did not move"
+
+
+def _run_steps(gpu, ts, n_steps, batch=None, **hyper):
+    # the C struct carries fp32 hyper-parameters: hand the oracle the same rounded values
+    hp = {k: float(np.float32(v)) for k, v in dict(HYPER, **hyper).items()}
+    tr = _trainer(gpu, ts, **hyper)
+    oh = _oracle_head(ts)
+    w_before = [p.copy() for p in oh.params()]
+    bar = _Bar(w_before)
+    B = ts.x.shape[0]
+    for s in range(n_steps):
+        rows = None
+        if batch is not None:
+            lo = (s * batch) % B
+            rows = slice(lo, min(lo + batch, B))
+        sl = slice(None) if rows is None else rows
+        wgt = _weights(ts)
+        loss_o, gs = oracle.head_loss_grad(ts.x[sl], ts.bins[sl], ts.y[sl], oh, hp["lam"],
+                                           None if wgt is None else wgt[sl])
+        loss_o2 = oracle.train_step(ts.x[sl], ts.bins[sl], ts.y[sl], oh, hp["lam"], hp["lr"], hp["beta1"],
+                                    hp["beta2"], hp["eps"], hp["weight_decay"], None if wgt is None else wgt[sl])
+        assert np.array_equal(loss_o, loss_o2)
+        tight = bar.add_step(oh, gs, hp, s + 1)
+        loss_g = _gpu_step(gpu, tr, ts, rows)
+        assert np.all(np.abs(loss_g - loss_o) <= 2e-5 * np.abs(loss_o) + 1e-12), (loss_g, loss_o)
+        for i, n in enumerate(NAMES):
+            gg = tr.grads[n].cpu().numpy()
+            r = rel_l2(gg, gs[i])
+            assert r <= 2e-5, f"step {s}: grad {n} rel L2 {r}"
+            assert np.all(gg[gs[i] == 0.0] == 0.0)
+        _check_params(tr, oh, bar, tight, gs, hp, w_before)
+    return tr, oh
+
+
+def test_one_step_ragged_shapes(gpu):
+    # d_h, B and K leave partial tiles everywhere (64-wide tiles, 16-sample stages)
+    ts = wl.make_train(11, B=37, d=256, d_h=96, K=20)
+    _run_steps(gpu, ts, 1)
+
+
+def test_several_steps_minibatches(gpu):
+    ts = wl.make_train(12, B=64, d=128, d_h=200, K=20)
+    _run_steps(gpu, ts, 6, batch=16)
+
+
+def test_larger_learning_rate_and_no_decay(gpu):
+    ts = wl.make_train(13, B=33, d=64, d_h=70, K=7)
+    _run_steps(gpu, ts, 4, lr=1e-3, weight_decay=0.0, lam=0.5)
+
+
+def test_pure_cross_entropy_and_pure_mse(gpu):
+    ts = wl.make_train(14, B=20, d=64, d_h=64, K=20)
+    _run_steps(gpu, ts, 2, lam=1.0)
+    _run_steps(gpu, ts, 2, lam=0.0)
+
+
+def test_plp_step_average_weights(gpu):
+    # Eq. 9: samples are decode steps of 9 sequences; each sequence's steps share its 1/N
+    ts = wl.make_train(15, B=41, d=128, d_h=96, K=20, plp_seqs=9)
+    assert abs(_weights(ts).sum() - 1.0) < 1e-12
+    _run_steps(gpu, ts, 2)
+
+
+def test_paper_batch_full_width(gpu):
+    # batch of 16, d = 4096, d_h = 1024, K = 20: the shape the experimental setup trains at
+    ts = wl.make_train(16, B=16, d=4096, d_h=1024, K=20)
+    _run_steps(gpu, ts, 2)
+
+
+def test_single_sample_and_single_bin(gpu):
+    ts = wl.make_train(17, B=1, d=64, d_h=32, K=20)
+    _run_steps(gpu, ts, 1)
+    # K = 1: softmax of one logit is 1, yhat = c_1 whatever the parameters, every gradient is 0
+    ts = wl.make_train(18, B=8, d=64, d_h=32, K=1)
+    tr = _trainer(gpu, ts, weight_decay=0.0)
+    before = {n: tr.params[n].clone() for n in NAMES}
+    loss = _gpu_step(gpu, tr, ts)
+    want_mse = np.mean((ts.y.astype(np.float64) - float(ts.centers[0])) ** 2)
+    assert abs(loss[1]) <= 1e-6 and abs(loss[2] - want_mse) <= 1e-5 * want_mse
+    for n in NAMES:
+        assert float(tr.grads[n].abs().max()) == 0.0
+        assert bool((tr.params[n] == before[n]).all())
+
+
+def test_bit_reproducible(gpu):
+    import torch
+    ts = wl.make_train(19, B=50, d=256, d_h=128, K=20)
+    outs = []
+    for _ in range(2):
+        tr = _trainer(gpu, ts)
+        for _ in range(3):
+            loss = _gpu_step(gpu, tr, ts)
+        outs.append((loss, {n: tr.params[n].clone() for n in NAMES}))
+    assert np.array_equal(outs[0][0], outs[1][0])
+    for n in NAMES:
+        assert torch.equal(outs[0][1][n], outs[1][1][n])
+
+
+def test_loss_goes_down_and_trained_head_scores(gpu):
+    # a few hundred steps at a visible learning rate: the joint loss falls, and the trained
+    # parameters, used as a K-bin scoring head (Eq. 6), predict what the oracle's head predicts
+    import torch
+    ts = wl.make_train(20, B=64, d=64, d_h=64, K=20)
+    tr = _trainer(gpu, ts, keep_grads=False, lr=2e-3)
+    td = gpu.to_device
+    x, bins, y = td(ts.x), td(ts.bins), td(ts.y)
+    first = tr.step(x, bins, y).cpu().numpy().copy()
+    for _ in range(300):
+        last = tr.step(x, bins, y)
+    last = last.cpu().numpy()
+    assert last[0] < 0.7 * first[0] and last[1] < first[1]
+
+    # score a ragged batch whose hidden states are such that pooling is trivial (one token per
+    # sequence: pooled = the token), with the trained head; compare with the oracle's head on the
+    # GPU-trained parameters
+    w = wl.make(wl.scaled(wl.SPECS["tiny"], B=8, d=64, d_h=64, lengths=tuple([1] * 8)))
+    p = {n: tr.params[n].cpu().numpy() for n in NAMES}
+    sc = gpu.Scorer(td(w.w_lm), tr.as_head())
+    off = torch.arange(9, dtype=torch.int32, device="cuda")
+    out = sc.score(td(w.hidden), off)
+    head = oracle.Head(p["w1"], p["w2"], p["b1"], p["b2"], ts.centers)
+    want = oracle.egtp(w.hidden, np.arange(9, dtype=np.int32), w.w_lm, head)
+    assert_pred_close(out["pred"].cpu().numpy(), want.pred)
+    sc.close()
+
+
+def test_argument_errors(gpu):
+    import torch
+    ts = wl.make_train(21, B=8, d=64, d_h=32, K=20)
+    td = gpu.to_device
+    x, bins, y = td(ts.x), td(ts.bins), td(ts.y)
+    for bad, code in ((dict(lam=1.5), 9), (dict(lr=-1.0), 9), (dict(beta1=1.0), 9), (dict(beta2=-0.1), 9),
+                      (dict(eps=0.0), 9), (dict(weight_decay=-1.0), 9)):
+        tr = _trainer(gpu, ts, **bad)
+        with pytest.raises(gpu.EgtpError) as e:
+            tr.step(x, bins, y)
+        assert e.value.status == code
+    tr = _trainer(gpu, ts)
+    before = tr.params["w1"].clone()
+    h = tr._struct()
+    h.t = 0
+    ws = torch.empty(gpu.egtp_head_train_workspace_bytes(8, 64, 32, 20), dtype=torch.uint8, device="cuda")
+    with pytest.raises(gpu.EgtpError) as e:
+        gpu.egtp_head_train_step(h, x, bins, y, None, 0, 8, ws, tr.loss)
+    assert e.value.status == 9
+    h.t = 1
+    with pytest.raises(gpu.EgtpError) as e:                      # workspace too small
+        gpu.egtp_head_train_step(h, x, bins, y, None, 0, 8, ws[:256], tr.loss)
+    assert e.value.status == 5
+    with pytest.raises(gpu.EgtpError) as e:                      # missing targets
+        gpu.egtp_head_train_step(h, x, bins, None, None, 0, 8, ws, tr.loss)
+    assert e.value.status == 1
+    with pytest.raises(gpu.EgtpError) as e:                      # step counts without a sequence count
+        gpu.egtp_head_train_step(h, x, bins, y, bins, 0, 8, ws, tr.loss)
+    assert e.value.status == 2
+    h.d = 62
+    with pytest.raises(gpu.EgtpError) as e:
+        gpu.egtp_head_train_step(h, x, bins, y, None, 0, 8, ws, tr.loss)
+    assert e.value.status == 2
+    assert gpu.egtp_head_train_workspace_bytes(8, 62, 32, 20) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(tr.params["w1"], before)                  # nothing was launched
+    h.d = 64
+    gpu.egtp_head_train_step(h, x, bins, y, None, 0, 0, None, None)   # B = 0: nothing to do
