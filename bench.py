@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E peak
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k1_entropy_bf16_serving_hbm_traffic.txt")
@@ -87,13 +88,49 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
     return 0
 
 
+def bench_train(args, gpu, wl, np, torch) -> int:
+    """Head training workload: one step = egtp_head_train_step on a batch of 16 pooled vectors
+    (d = 4096, d_h = 1024, K = 20; batch size, K and optimiser of the paper's experimental setup).
+    At this batch the step is a stream over W1 and its two AdamW moments (each read and written
+    once: 6 x 4 x d_h x d bytes), so the roofline is HBM."""
+    B, d, d_h, K = args.train_batch, 4096, 1024, 20
+    sets = [wl.make_train(100 + i, B, d, d_h, K) for i in range(4)]
+    td = gpu.to_device
+    ts = sets[0]
+    tr = gpu.HeadTrainer(td(ts.w1), td(ts.b1), td(ts.w2), td(ts.b2), td(ts.centers))
+    batches = [(td(t.x), td(t.bins), td(t.y)) for t in sets]
+    steps = args.steps if args.steps != 10 else 200
+    for i in range(max(args.warmup, 1)):
+        tr.step(*batches[i % 4])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        tr.step(*batches[i % 4])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    bytes_w1 = 6.0 * 4.0 * d_h * d
+    achieved = bytes_w1 * steps / dt / 1e9
+    print(json.dumps({
+        "metric": "head training samples/sec (Eq. 5/7 + AdamW step, batch 16, d=4096 d_h=1024 K=20)",
+        "value": B * steps / dt, "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"train: batch {B}, d={d}, d_h={d_h}, K={K}, lambda 0.95, AdamW lr 2e-5", "B": B},
+        "roofline": {"kernel": "whole step (dominated by train_w1_update: W1 + two moments streamed once)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
+        "cpu_baseline": None}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode"],
+    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "train"],
                     help="serving = the workload the headline metric is quoted on (default)")
+    ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
     ap.add_argument("--oracle-tokens", type=int, default=256, help="tokens of the CPU-baseline sample (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference dispatch for "
@@ -112,6 +149,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.workload == "plp_decode":
         return bench_plp(args, gpu, wl, np, torch)
+    if args.workload == "train":
+        return bench_train(args, gpu, wl, np, torch)
     spec = wl.SPECS[args.workload]
     t0 = time.time()
     w = wl.make(spec)

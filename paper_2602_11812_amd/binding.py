@@ -8,7 +8,8 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+from ctypes import (POINTER, Structure, byref, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_size_t,
+                    c_void_p)
 from typing import Optional
 
 import numpy as np
@@ -24,7 +25,7 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
            "egtp_profile_enable", "egtp_profile_read", "egtp_packed_w_lm_bytes", "egtp_pack_w_lm",
-           "egtp_head_train_workspace_bytes", "egtp_head_train_step")
+           "egtp_head_train_workspace_bytes", "egtp_head_train_step", "egtp_sjf_order", "egtp_simulate_batches")
 
 
 class egtp_head(Structure):
@@ -47,6 +48,12 @@ class egtp_head_train(Structure):
                 ("lambda_", c_float), ("lr", c_float), ("beta1", c_float), ("beta2", c_float),
                 ("eps", c_float), ("weight_decay", c_float), ("t", c_int64),
                 ("g_w1", c_void_p), ("g_b1", c_void_p), ("g_w2", c_void_p), ("g_b2", c_void_p)]
+
+
+class egtp_sched_report(Structure):
+    _fields_ = [("n_batches", c_int32), ("actual_tokens", c_int64), ("allocated_tokens", c_int64),
+                ("makespan_steps", c_int64), ("sum_jct_steps", c_int64), ("padding_ratio", c_double),
+                ("avg_jct_steps", c_double), ("throughput", c_double)]
 
 
 class EgtpError(RuntimeError):
@@ -98,6 +105,10 @@ def load_library() -> ctypes.CDLL:
     lib.egtp_head_train_workspace_bytes.restype = c_size_t
     lib.egtp_head_train_step.argtypes = [POINTER(egtp_head_train), vp, vp, vp, vp, i32, i32, vp, c_size_t, vp, vp]
     lib.egtp_head_train_step.restype = c_int
+    lib.egtp_sjf_order.argtypes = [vp, i32, vp]
+    lib.egtp_sjf_order.restype = c_int
+    lib.egtp_simulate_batches.argtypes = [vp, vp, i32, i32, POINTER(egtp_sched_report), vp, vp]
+    lib.egtp_simulate_batches.restype = c_int
     _lib = lib
     return lib
 
@@ -255,6 +266,31 @@ def egtp_head_train_step(head: egtp_head_train, x, bin, y, steps_per_seq, n_seqs
                                              _dev(loss_out), _stream(stream))
     if st != EGTP_OK:
         raise EgtpError(st, "egtp_head_train_step")
+
+
+# --------------------------------------------------------------------------- host-side scheduling model
+def egtp_sjf_order(pred) -> np.ndarray:
+    """Shortest-predicted-job-first permutation of host predictions (fp32)."""
+    p = np.ascontiguousarray(np.asarray(pred, dtype=np.float32))
+    order = np.empty(p.size, dtype=np.int32)
+    st = load_library().egtp_sjf_order(_host_ptr(p), p.size, _host_ptr(order))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_sjf_order")
+    return order
+
+
+def egtp_simulate_batches(order, true_len, batch_size: int):
+    """Returns (egtp_sched_report, completion_step[n] int64, batch_of[n] int32)."""
+    o, t = _host_i32(order), _host_i32(true_len)
+    n = t.size
+    rep = egtp_sched_report()
+    done = np.zeros(n, dtype=np.int64)
+    batch_of = np.zeros(n, dtype=np.int32)
+    st = load_library().egtp_simulate_batches(_host_ptr(o), _host_ptr(t), n, int(batch_size), byref(rep),
+                                              _host_ptr(done), _host_ptr(batch_of))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_simulate_batches")
+    return rep, done, batch_of
 
 
 # --------------------------------------------------------------------------- convenience (memory only)
