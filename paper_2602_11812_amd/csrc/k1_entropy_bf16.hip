@@ -1,14 +1,14 @@
 // Fused LM-head contraction + streaming entropy for bf16 inputs on gfx950 (Eq. 2).
 //
 // logits^T = W_lm . hidden^T is computed tile by tile on the bf16 matrix cores with the
-// vocabulary as the MFMA row dimension and the tokens as its column dimension.  With the
-// 32x32 accumulator layout every lane then holds logits of ONE token (its column) for
-// 16 vocabulary rows per MFMA tile, so the softmax statistics of a token
+// vocabulary as the MFMA row dimension and the tokens as its column dimension.  In the
+// 16x16 accumulator layout a lane holds rows 4*(l/16)+i of column l%16, i.e. logits of ONE
+// token (its column), so the softmax statistics of a token
 //     m = max z,  S = sum e^{z-m},  U = sum e^{z-m} (z-m) log2(e)
-// are carried in registers, lane-private, across the whole vocabulary sweep, and lanes are
-// only combined once at the end.  Logits never leave the register file:
-// H = ln S - U ln2 / S  is finished by the merge kernel from one triple per
-// (token, vocabulary range).
+// are carried in registers, lane-private, across the whole vocabulary sweep, and the four
+// lanes and two waves that share a token are only combined once at the end.  Logits never
+// leave the register file:  H = ln S - U ln2 / S  is finished by the merge kernel from one
+// triple per (token, vocabulary range).
 //
 // Both operands are read from a PACKED copy: 256 rows x 32 K-elements per block of 16 KiB,
 // stored exactly as the block sits in LDS (16-byte chunks XOR-swizzled by row so that the
@@ -16,22 +16,25 @@
 // 16 KiB read, which is what HBM and the Infinity Cache want; reading 64-byte row pieces
 // with a row stride of 2d bytes from the row-major matrices stalls the ring on DRAM page
 // misses.  pack_rows_bf16 builds the packed copy (W_lm once, hidden states once per call;
-// rows and K are zero-padded to whole blocks).
+// rows are zero-padded to whole blocks, K to an even number of blocks).
 //
 // Workgroup = 256 threads = 4 waves (2 along vocabulary x 2 along tokens), macro tile
-// 256 vocabulary rows x 256 tokens, each wave 128 x 128 = 4x4 MFMA 32x32x16 tiles
-// (256 accumulator registers).  Blocks go from global memory straight into an NSTAGE-deep
-// LDS ring (16 bytes per lane, no staging registers).  One wave per SIMD means nothing
-// hides a stall, so the instruction order inside a K step is pinned: every MFMA is followed
-// by one load or one fragment read, which then issues in the shadow of the MFMA.  The one
-// barrier per step sits between the two K sub-steps, after the reads of the current stage
-// and before the fragments of the next step are fetched.
+// 256 vocabulary rows x 256 tokens, each wave 128 x 128 = 8x8 MFMA 16x16x32 tiles
+// (256 accumulator registers); one 16-byte fragment read covers a whole K step: lane l
+// holds row l%16, chunk l/16 of the 64-byte row.  Blocks go from global memory straight
+// into an NSTAGE-deep LDS ring (16 bytes per lane, no staging registers).  The kernel runs
+// at the package power limit, so what counts is energy per FLOP: the 16x16x32 shape with the
+// first operand held for 8 consecutive MFMAs (row-major tile order) draws markedly less
+// power than 32x32x16 or than any order that changes both operands every MFMA.  One wave
+// per SIMD means nothing hides a stall, so the instruction order inside a K step is pinned:
+// loads and fragment reads are spread between the MFMAs, which cover them.  The one barrier
+// per step sits between the step's two halves, after the last read of the current stage.
 #include "kernels.h"
 
 namespace egtp {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
@@ -51,6 +54,10 @@ static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geome
 struct Stats {
     float m, S, U;
 };
+
+// K steps of a sweep over d: K is zero-padded to a multiple of two steps, so that the main loop
+// can be unrolled by two (the fragment registers swap roles every step).
+__host__ __device__ __forceinline__ int k_steps(int d) { return 2 * ((d + 2 * BK - 1) / (2 * BK)); }
 
 // XOR key of a row's four 16-byte chunks inside a packed block (64-byte rows).  A fragment read
 // takes the same logical chunk of consecutive rows; with this key any 16 consecutive rows fall
@@ -73,18 +80,35 @@ __device__ __forceinline__ Stats merge(Stats a, Stats b)
     return r;
 }
 
-// Fold the 16 logits a lane holds for one token column in one MFMA tile into the running
-// statistics of that token.  MASK: only vocabulary rows < V count (the zero rows that pad
-// the last tile are excluded).  row0 is the vocabulary row of element 0 for this lane.
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
+// [3:0] and [15:14], export and LDS/scalar counters left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wave lands at
+// lds_wave_base + 16 * i.
+__device__ __forceinline__ void load16_to_lds(const unsigned char *g, unsigned char *lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// scheduling-group masks of the AMDGPU backend
+constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100;
+
+// Fold 16 logits of one token: zin[4*q+i] is vocabulary row row0 + 16*q + i.
 template <bool MASK>
-__device__ __forceinline__ void fold_tile(const f32x16 &a, Stats &st, int row0, int V)
+__device__ __forceinline__ void fold16(const float (&zin)[16], Stats &st, int row0, int V)
 {
     float z[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        float v = a[i];
+        float v = zin[i];
         if (MASK)
-            v = (row0 + 8 * (i >> 2) + (i & 3)) < V ? v : NEG_BIG;
+            v = (row0 + 16 * (i >> 2) + (i & 3)) < V ? v : NEG_BIG;
         z[i] = v;
     }
     float mx = z[0];
@@ -116,25 +140,6 @@ __device__ __forceinline__ void fold_tile(const f32x16 &a, Stats &st, int row0, 
     st.S += S0 + S1;
     st.U += U0 + U1;
 }
-
-// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
-// [3:0] and [15:14], export and LDS/scalar counters left at their maxima)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane i of the wave lands at
-// lds_wave_base + 16 * i.
-__device__ __forceinline__ void load16_to_lds(const unsigned char *g, unsigned char *lds_wave_base)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
-}
-
-// scheduling-group masks of the AMDGPU backend
-constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100;
 
 template <int NSTAGE>
 __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
@@ -188,18 +193,18 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         }
     };
 
-    // ---- fragment read geometry (row r, chunk c sits at r*64 + ((c ^ swizzle_key(r)) * 16)) ----
-    const int l31 = lane & 31;
-    const int khalf = lane >> 5;
-    const unsigned fragA = (unsigned)(wm * 128 + l31) * ROW_BYTES;
-    const unsigned fragB = (unsigned)TILE_BYTES + (unsigned)(wn * 128 + l31) * ROW_BYTES;
-    const int swf = swizzle_key(l31);  // row = l31 + a multiple of 32
-    const unsigned swz0 = (unsigned)(((0 + khalf) ^ swf) << 4);
-    const unsigned swz1 = (unsigned)(((2 + khalf) ^ swf) << 4);
+    // ---- fragment read geometry: row r, chunk c sits at r*64 + ((c ^ swizzle_key(r)) * 16); the key
+    //      of row 16*t + l15 is the key of l15
+    const int l15 = lane & 15;
+    const int kq = lane >> 4;
+    const unsigned swz = (unsigned)((kq ^ swizzle_key(l15)) << 4);
+    const unsigned fragA = (unsigned)(wm * 128 + l15) * ROW_BYTES + swz;
+    const unsigned fragB = (unsigned)TILE_BYTES + (unsigned)(wn * 128 + l15) * ROW_BYTES + swz;
+    constexpr int FRAG_STRIDE = 16 * ROW_BYTES;  // 16 rows further
 
-    Stats st[4];
+    Stats st[8];
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
+    for (int ni = 0; ni < 8; ++ni) {
         st[ni].m = NEG_BIG;
         st[ni].S = 0.f;
         st[ni].U = 0.f;
@@ -225,126 +230,171 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
 
-    bf16x8 fa[2][4], fb[2][4];
-#define EGTP_READ_FRAGS(set_, stage_base_, swz_)                                                  \
-    {                                                                                             \
-        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                          \
-            fa[set_][mi] = *(const bf16x8 *)((stage_base_) + fragA + mi * 32 * ROW_BYTES + swz_); \
-        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                          \
-            fb[set_][ni] = *(const bf16x8 *)((stage_base_) + fragB + ni * 32 * ROW_BYTES + swz_); \
-    }
-#define EGTP_MFMA_PHASE(set_)                                                                     \
-    {                                                                                             \
-        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                          \
-            _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                      \
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set_][mi], fb[set_][ni], \
-                                                                      acc[mi][ni], 0, 0, 0);      \
-    }
-    EGTP_READ_FRAGS(0, smem, swz0);
+    // Fragments of the current step: rows 0..63 (fa0) and 64..127 (fa1) of the wave tile, re-read in
+    // place once their half is done, and two sets of 8 column fragments that swap roles every step.
+    bf16x8 fa0[4], fa1[4], fbA[8], fbB[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        fa0[i] = *(const bf16x8 *)(smem + fragA + i * FRAG_STRIDE);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        fbA[i] = *(const bf16x8 *)(smem + fragB + i * FRAG_STRIDE);
 
     int ldstage = NSTAGE - 1;  // stage the next loads go to
     int cstage = 0;            // stage being consumed
-    for (int vt = vt_begin; vt < vt_end; ++vt) {
-        f32x16 acc[4][4];
+    f32x4 acc[8][8];
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
+        for (int ni = 0; ni < 8; ++ni)
 #pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    acc[mi][ni][i] = 0.f;
+            for (int i = 0; i < 4; ++i)
+                acc[mi][ni][i] = 0.f;
 
-        for (int kt = 0; kt < KT; ++kt) {
-            const unsigned char *sA = smem + cstage * STAGE_BYTES;
-            const int nstage = cstage + 1 == NSTAGE ? 0 : cstage + 1;
-            const unsigned char *sN = smem + nstage * STAGE_BYTES;
-            // ---- first half: loads for the step NSTAGE-1 ahead (into the stage consumed in
-            //      the previous step), fragments of sub-step 1, MFMAs of sub-step 0
-            issue_loads(lvt, lkt, ldstage);
-            advance_ld();
-            ldstage = ldstage + 1 == NSTAGE ? 0 : ldstage + 1;
-            EGTP_READ_FRAGS(1, sA, swz1);
-            EGTP_MFMA_PHASE(0);
-#pragma unroll
-            for (int j = 0; j < LOADS_PER_STEP; ++j) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, 1, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-            }
-            // ---- the next step's blocks have landed (own loads; the newest NSTAGE-2 steps may
-            //      still be in flight), then everyone's.  Every read of the current stage has
-            //      been consumed by now.  A bare barrier: a fence would drain the whole ring.
-            wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();
-            __builtin_amdgcn_s_barrier();
-            // ---- second half: fragments of the next step's sub-step 0, MFMAs of sub-step 1
-            EGTP_READ_FRAGS(0, sN, swz0);
-            EGTP_MFMA_PHASE(1);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-            }
-            cstage = nstage;
+    // MFMA order is row-major throughout: the first operand stays the same for 8 MFMAs in a row,
+    // which this shape rewards with markedly lower power than changing both operands every time.
+    //
+    // First half of a step: rows 0..63.  The loads for the step NSTAGE-1 ahead (into the stage
+    // consumed in the previous step) and the row fragments of the second half issue in between.
+#define EGTP_HALF0(fb)                                                                                 \
+    {                                                                                                  \
+        const unsigned char *sA = smem + cstage * STAGE_BYTES;                                         \
+        issue_loads(lvt, lkt, ldstage);                                                                \
+        advance_ld();                                                                                  \
+        ldstage = ldstage + 1 == NSTAGE ? 0 : ldstage + 1;                                             \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
+            fa1[i] = *(const bf16x8 *)(sA + fragA + (4 + i) * FRAG_STRIDE);                            \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                               \
+            _Pragma("unroll") for (int ni = 0; ni < 8; ++ni)                                           \
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa0[mi], fb[ni], acc[mi][ni], 0, 0, 0); \
+        _Pragma("unroll") for (int j = 0; j < LOADS_PER_STEP; ++j) {                                   \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2, 0);                                       \
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, 1, 0);                                  \
+        }                                                                                              \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2, 0);                                       \
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                                    \
+        }                                                                                              \
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 8, 0);                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                             \
+    }
+    // The next step's blocks have landed (own loads; the newest NSTAGE-2 steps may still be in
+    // flight), then everyone's; every read of the current stage has been issued and, being
+    // consumed by the MFMAs above, completed.  A bare barrier: a fence would drain the whole ring.
+#define EGTP_STEP_BARRIER()                                                                            \
+    {                                                                                                  \
+        wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();                                                   \
+        __builtin_amdgcn_s_barrier();                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                             \
+    }
+    // Second half: rows 64..127.  The next step's fragments come from the next stage: rows 0..63
+    // into their own registers (free by now), the column fragments into the other set.
+#define EGTP_HALF1(fb, fbn)                                                                                 \
+    {                                                                                                  \
+        const int nstage = cstage + 1 == NSTAGE ? 0 : cstage + 1;                                      \
+        const unsigned char *sN = smem + nstage * STAGE_BYTES;                                         \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
+            fa0[i] = *(const bf16x8 *)(sN + fragA + i * FRAG_STRIDE);                                  \
+        _Pragma("unroll") for (int ni = 0; ni < 8; ++ni)                                               \
+            fbn[ni] = *(const bf16x8 *)(sN + fragB + ni * FRAG_STRIDE);                                \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                               \
+            _Pragma("unroll") for (int ni = 0; ni < 8; ++ni)                                           \
+                acc[4 + mi][ni] =                                                                      \
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa1[mi], fb[ni], acc[4 + mi][ni], 0, 0, 0); \
+        _Pragma("unroll") for (int j = 0; j < 12; ++j) {                                               \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2, 0);                                       \
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                                    \
+        }                                                                                              \
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 8, 0);                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                             \
+        cstage = nstage;                                                                               \
+    }
+
+    // The loop body is rotated by half a step -- [barrier, second half of step s, first half of
+    // step s+1] -- so that the fragments fetched last (the column fragments) have a whole half
+    // step to land before the back edge, where the compiler's wait is a conservative one.
+    EGTP_HALF0(fbA);
+    for (int vt = vt_begin; vt < vt_end; ++vt) {
+        // two steps per trip: the column fragment sets swap roles every step (KT is even)
+        for (int kt = 0; kt + 2 < KT; kt += 2) {
+            EGTP_STEP_BARRIER();
+            EGTP_HALF1(fbA, fbB);
+            EGTP_HALF0(fbB);
+            EGTP_STEP_BARRIER();
+            EGTP_HALF1(fbB, fbA);
+            EGTP_HALF0(fbA);
         }
+        EGTP_STEP_BARRIER();
+        EGTP_HALF1(fbA, fbB);
+        EGTP_HALF0(fbB);
+        EGTP_STEP_BARRIER();
+        EGTP_HALF1(fbB, fbA);
 
         // a full tile of logits is in registers: fold it into the statistics and forget it
-        const int row_base = vt * BM + wm * 128 + 4 * khalf;
-        if (vt * BM + BM > V) {
+        const int row_base = vt * BM + wm * 128 + 4 * kq;
+        const bool masked = vt * BM + BM > V;
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
+        for (int ni = 0; ni < 8; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    fold_tile<true>(acc[mi][ni], st[ni], row_base + mi * 32, V);
-        } else {
+            for (int h = 0; h < 2; ++h) {
+                float z[16];
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    fold_tile<false>(acc[mi][ni], st[ni], row_base + mi * 32, V);
+                    for (int i = 0; i < 4; ++i) {
+                        z[4 * q + i] = acc[4 * h + q][ni][i];
+                        acc[4 * h + q][ni][i] = 0.f;
+                    }
+                if (masked)
+                    fold16<true>(z, st[ni], row_base + h * 64, V);
+                else
+                    fold16<false>(z, st[ni], row_base + h * 64, V);
+            }
         }
+        if (vt + 1 < vt_end)
+            EGTP_HALF0(fbA);  // first half of the next tile's first step
     }
-#undef EGTP_READ_FRAGS
-#undef EGTP_MFMA_PHASE
+#undef EGTP_HALF0
+#undef EGTP_HALF1
+#undef EGTP_STEP_BARRIER
 
-    // drain the ring (the tail re-reads) before its memory is reused
     wait_vmcnt<0>();
     __syncthreads();
 
-    // ---- combine the lanes and waves that hold the same token ----------------------------
+    // ---- combine the four lanes, then the two waves, that hold the same token -------------
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        Stats o;
-        o.m = __shfl_xor(st[ni].m, 32);
-        o.S = __shfl_xor(st[ni].S, 32);
-        o.U = __shfl_xor(st[ni].U, 32);
-        st[ni] = merge(st[ni], o);
+    for (int ni = 0; ni < 8; ++ni) {
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            Stats o;
+            o.m = __shfl_xor(st[ni].m, off);
+            o.S = __shfl_xor(st[ni].S, off);
+            o.U = __shfl_xor(st[ni].U, off);
+            st[ni] = merge(st[ni], o);
+        }
     }
-    float *red = (float *)smem;  // [wn][ni][32][3]
-    if (wm == 1 && lane < 32) {
+    float *red = (float *)smem;  // [wn][ni][16][3]
+    if (wm == 1 && lane < 16) {
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            float *r = red + ((wn * 4 + ni) * 32 + lane) * 3;
+        for (int ni = 0; ni < 8; ++ni) {
+            float *r = red + ((wn * 8 + ni) * 16 + lane) * 3;
             r[0] = st[ni].m;
             r[1] = st[ni].S;
             r[2] = st[ni].U;
         }
     }
     __syncthreads();
-    if (wm == 0 && lane < 32) {
+    if (wm == 0 && lane < 16) {
         const long plane = (long)nsplit * T;
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const float *r = red + ((wn * 4 + ni) * 32 + lane) * 3;
+        for (int ni = 0; ni < 8; ++ni) {
+            const float *r = red + ((wn * 8 + ni) * 16 + lane) * 3;
             Stats o;
             o.m = r[0];
             o.S = r[1];
             o.U = r[2];
             Stats f = merge(st[ni], o);
-            const long tok = tok0 + wn * 128 + ni * 32 + lane;
+            const long tok = tok0 + wn * 128 + ni * 16 + lane;
             if (tok < T) {
                 const long idx = (long)sp * T + tok;
                 part[idx] = f.m;
@@ -443,7 +493,7 @@ __global__ __launch_bounds__(256) void pack_rows_bf16_kernel(const unsigned char
 size_t k1_packed_bytes(int64_t rows, int d)
 {
     const int64_t tiles = (rows + 255) / 256;
-    const int64_t kt = (d + BK - 1) / BK;
+    const int64_t kt = k_steps(d);
     return (size_t)(tiles * kt) * TILE_BYTES;
 }
 
@@ -452,7 +502,7 @@ hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hi
     if (rows <= 0)
         return hipSuccess;
     const long tiles = (rows + 255) / 256;
-    const int kt = (d + BK - 1) / BK;
+    const int kt = k_steps(d);
     if (tiles > 0x7fffffffL)
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(pack_rows_bf16_kernel, dim3((unsigned)tiles, (kt + 7) / 8), dim3(256), 0, st,
@@ -478,7 +528,7 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
     const long units = (long)p.ntb * p.nsplit;
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
-    const int kt = (d + BK - 1) / BK;
+    const int kt = k_steps(d);
     hipLaunchKernelGGL((k1_entropy_bf16_kernel<NSTAGE>), dim3((unsigned)units), dim3(256), LDS_BYTES, st,
                        (const unsigned char *)w_packed, (const unsigned char *)hidden_packed, (long)T, kt, V,
                        p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part);

@@ -29,8 +29,9 @@ size_t k1_partial_floats(const K1Plan &p, int64_t T);
 size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
 
 // Packed operand layout of the bf16 matrix-core kernel: blocks of 256 rows x K1_PACK_K
-// elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * ceil(d/K) + step,
-// stored in LDS-image order; rows and K zero-padded to whole blocks.
+// elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * steps + step with
+// steps = 2 * ceil(d / (2 K)) (an even number), stored in LDS-image order; rows and K zero-padded
+// to whole blocks.
 constexpr int K1_PACK_K = 32;
 constexpr int K1_PACK_BLOCK_BYTES = 256 * K1_PACK_K * 2;
 size_t k1_packed_bytes(int64_t rows, int d);
