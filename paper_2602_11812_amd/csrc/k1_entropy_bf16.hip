@@ -59,11 +59,11 @@ struct Stats {
 // can be unrolled by two (the fragment registers swap roles every step).
 __host__ __device__ __forceinline__ int k_steps(int d) { return 2 * ((d + 2 * BK - 1) / (2 * BK)); }
 
-// XOR key of a row's four 16-byte chunks inside a packed block (64-byte rows).  A fragment read
-// takes the same logical chunk of consecutive rows; with this key any 16 consecutive rows fall
-// on 16 different 16-byte bank groups of a 256-byte LDS line, and any 8 consecutive rows on 8
-// different groups of a 128-byte line, so the reads are conflict-free either way.
-__host__ __device__ __forceinline__ int swizzle_key(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+// XOR key of a row's four 16-byte chunks inside a packed block (64-byte rows).  With the
+// fragment layout below (lane l reads row l%16 + 16t, chunk l/16) this key makes the 16-byte-per-
+// lane LDS reads as fast as a linear read; found by timing candidate keys on the hardware (most
+// others, the identity included, cost a third more LDS cycles per read).
+__host__ __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & 3; }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
