@@ -24,7 +24,7 @@ struct egtp_ctx {
 namespace egtp {
 
 // ---- geometry of the fused entropy kernel ------------------------------------------------
-static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 4096;
+static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 8192;
 static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
 
 K1Plan k1_plan(int dtype, int64_t T, int /*d*/, int V)
