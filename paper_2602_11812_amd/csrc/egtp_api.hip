@@ -106,7 +106,7 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     w.lse_new = cv.take<float>((size_t)B);
     w.state_scale = cv.take<float>((size_t)B);
     w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
-    w.act = cv.take<float>((size_t)head_k_splits(c.d) * (size_t)B * (size_t)dh);
+    w.act = cv.take<float>(head_act_floats_bound(c.d, dh, B));
     w.hidden_packed = nullptr;
     w.w_packed = nullptr;
     if (c.dtype == EGTP_BF16) {
@@ -532,7 +532,7 @@ TrainWorkspace carve_train(void *base, int32_t B, int32_t d, int32_t d_h, int32_
 {
     Carver cv(base);
     TrainWorkspace w;
-    w.act_part = cv.take<float>((size_t)head_k_splits(d) * (size_t)B * (size_t)d_h);
+    w.act_part = cv.take<float>(head_act_floats_bound(d, d_h, B));
     w.act = cv.take<float>((size_t)B * (size_t)d_h);
     w.dact = cv.take<float>((size_t)B * (size_t)d_h);
     w.dz = cv.take<float>((size_t)B * (size_t)K);

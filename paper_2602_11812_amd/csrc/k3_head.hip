@@ -3,7 +3,7 @@
 //
 // Layer 1 is a small [B x d] . [d x d_h] contraction kept entirely in fp32 (the pooled
 // vector is never re-rounded); it is LDS-tiled, 64 x 64 outputs per workgroup, 4 x 4 per
-// thread, and split along d (blockIdx.z) so that a few hundred workgroups exist even for one
+// thread, and split along d (blockIdx.z) so that about a thousand workgroups exist even for one
 // small batch; the splits leave partial pre-activations that layer 2 adds in split order
 // (fixed order, bit-reproducible) before bias and ReLU.  Layer 2 and the K-bin decode are one
 // wave per sequence.
@@ -158,10 +158,28 @@ __global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict
 
 }  // namespace
 
-int head_k_splits(int d)
+int head_k_splits(int d, int d_h, int32_t B)
 {
-    int n = (d + 511) / 512;
-    return n < 1 ? 1 : (n > 8 ? 8 : n);
+    int base = (d + 511) / 512;  // slices of at most 512 along d ...
+    base = base < 1 ? 1 : (base > 8 ? 8 : base);
+    const long tiles = (long)((d_h + TM - 1) / TM) * ((B + TN - 1) / TN);
+    long want = tiles > 0 ? (1024 + tiles - 1) / tiles : 1;  // ... thinner when the batch has few tiles
+    const int cap = (d + TK - 1) / TK < 64 ? (d + TK - 1) / TK : 64;
+    long n = want > base ? want : base;
+    n = n > cap ? cap : n;
+    return n < 1 ? 1 : (int)n;
+}
+
+size_t head_act_floats_bound(int d, int d_h, int32_t B)
+{
+    // the number of planes only depends on how many 64-sequence tiles the batch has
+    size_t best = 0;
+    for (int32_t st = 1; st <= (B + TN - 1) / TN; ++st) {
+        const int32_t b = st * TN < B ? st * TN : B;
+        const size_t f = (size_t)head_k_splits(d, d_h, b) * (size_t)b * (size_t)d_h;
+        best = f > best ? f : best;
+    }
+    return best;
 }
 
 hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, int d_h, const void *w1,
@@ -169,7 +187,7 @@ hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, in
 {
     if (B <= 0)
         return hipSuccess;
-    const int nks = head_k_splits(d);
+    const int nks = head_k_splits(d, d_h, B);
     const int kchunk = ((d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
     const dim3 grid((d_h + TM - 1) / TM, (B + TN - 1) / TN, nks);
     if (wdtype == DT_BF16)
@@ -185,7 +203,7 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
 {
     if (a.B <= 0)
         return hipSuccess;
-    const int nks = head_k_splits(a.d);
+    const int nks = head_k_splits(a.d, a.d_h, a.B);
     const size_t lds2 = (size_t)a.d_h * sizeof(float);
     if (lds2 > 64 * 1024)
         return hipErrorInvalidValue;

@@ -68,6 +68,7 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
 
     for (int j = tid; j < d_h; j += 256) {
         float pre = 0.f;
+#pragma unroll 8
         for (int s = 0; s < nks; ++s)
             pre += act_part[((long)s * B + b) * d_h + j];
         pre += b1[j];
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
     __syncthreads();
     for (int o = wave; o < K; o += 4) {
         float s = 0.f;
+#pragma unroll 8
         for (int j = lane; j < d_h; j += 64)
             s = fmaf(w2[(long)o * d_h + j], a[j], s);
         s = wave_sum(s) + b2[o];
@@ -127,6 +129,7 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
     __syncthreads();
     for (int j = tid; j < d_h; j += 256) {
         float s = 0.f;
+#pragma unroll 4
         for (int o = 0; o < K; ++o)
             s = fmaf(dz[o], w2[(long)o * d_h + j], s);
         dact[(long)b * d_h + j] = a[j] > 0.f ? s : 0.f;
@@ -299,7 +302,7 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     hipError_t e = head_layer1(a.x, nullptr, a.B, a.d, a.d_h, a.w1, DT_F32, a.act_part, st);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(train_sample_kernel, dim3(a.B), dim3(256), lds, st, a.act_part, head_k_splits(a.d), a.B,
+    hipLaunchKernelGGL(train_sample_kernel, dim3(a.B), dim3(256), lds, st, a.act_part, head_k_splits(a.d, a.d_h, a.B), a.B,
                        a.d_h, a.K, a.b1, a.w2, a.b2, a.centers, a.bin, a.y, a.steps, a.n_seqs, a.lambda, a.act,
                        a.dact, a.dz, a.loss_part);
     Adam h;

@@ -101,3 +101,19 @@ def test_null_context_is_an_error_not_a_crash(lib):
     assert lib.egtp_score(None, None, None, None, 1, 1, None, 0, None, None, None, None, None) == 1
     lib.plp_step.restype = ctypes.c_int
     assert lib.plp_step(None, None, None, None, None, 1, 1, None, None, None, 0, None, None, None) == 1
+
+
+def test_training_workspace_size_is_monotonic_and_rejects_bad_shapes(lib):
+    f = lib.egtp_head_train_workspace_bytes
+    f.restype = ctypes.c_size_t
+    f.argtypes = [ctypes.c_int32] * 4
+    prev = 0
+    for B in (0, 1, 15, 16, 63, 64, 65, 128, 129, 1000, 4096):
+        n = f(B, 4096, 1024, 20)
+        assert n >= prev and n % 256 == 0
+        # at least the activations, their gradients, dL/dz and the loss terms
+        assert n >= 4 * (2 * B * 1024 + B * 20 + 2 * B)
+        prev = n
+    assert f(16, 4094, 1024, 20) == 0        # feature size must be a multiple of 4
+    assert f(16, 4096, 0, 20) == 0 and f(16, 4096, 1024, 0) == 0 and f(-1, 4096, 1024, 20) == 0
+    assert f(16, 4096, 16385, 20) == 0 and f(16, 4096, 1024, 1025) == 0
