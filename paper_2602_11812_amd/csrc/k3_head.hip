@@ -6,7 +6,7 @@
 // thread, and split along d (blockIdx.z) so that about a thousand workgroups exist even for one
 // small batch; the splits leave partial pre-activations that layer 2 adds in split order
 // (fixed order, bit-reproducible) before bias and ReLU.  Layer 2 and the K-bin decode are one
-// wave per sequence.
+// workgroup per sequence.
 #include "kernels.h"
 
 namespace egtp {
@@ -107,32 +107,35 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// one wave per sequence: out[o] = b2[o] + w2[o,:] . act[b,:]; n_out > 1 => Eq. 6
+// one workgroup (4 waves) per sequence: out[o] = b2[o] + w2[o,:] . act[b,:]; n_out > 1 => Eq. 6
+// LDS: a[d_h] | partial[4][n_out]
 template <bool WBF16>
-__global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict__ act_part, int nks, int B,
-                                                         const float *__restrict__ b1, int d_h, int n_out,
-                                                         const void *__restrict__ w2,
-                                                         const float *__restrict__ b2,
-                                                         const float *__restrict__ centers,
-                                                         float *__restrict__ pred)
+__global__ __launch_bounds__(256) void head_layer2_kernel(const float *__restrict__ act_part, int nks, int B,
+                                                          const float *__restrict__ b1, int d_h, int n_out,
+                                                          const void *__restrict__ w2,
+                                                          const float *__restrict__ b2,
+                                                          const float *__restrict__ centers,
+                                                          float *__restrict__ pred)
 {
     const int b = blockIdx.x;
-    const int lane = threadIdx.x;
-    // hidden activations: partial sums in split order, then bias and ReLU; kept in LDS
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     extern __shared__ float a[];
-    for (int j = lane; j < d_h; j += 64) {
+    float *partial = a + d_h;
+    // hidden activations: partial sums in split order, then bias and ReLU; kept in LDS
+    for (int j = tid; j < d_h; j += 256) {
         float pre = 0.f;
+#pragma unroll 8
         for (int z = 0; z < nks; ++z)
             pre += act_part[((long)z * B + b) * d_h + j];
         pre += b1 ? b1[j] : 0.f;
         a[j] = pre > 0.f ? pre : 0.f;
     }
     __syncthreads();
-    // online softmax-expectation over the n_out outputs (every lane carries the same values)
-    float m = -__builtin_inff(), den = 0.f, num = 0.f, y = 0.f;
+    // every wave takes a quarter of each dot product (fixed assignment: bit-reproducible)
     for (int o = 0; o < n_out; ++o) {
         float s = 0.f;
-        for (int j = lane; j < d_h; j += 64) {
+#pragma unroll 4
+        for (int j = tid; j < d_h; j += 256) {
             float w;
             if (WBF16)
                 w = __uint_as_float((unsigned)((const unsigned short *)w2)[(long)o * d_h + j] << 16);
@@ -140,7 +143,18 @@ __global__ __launch_bounds__(64) void head_layer2_kernel(const float *__restrict
                 w = ((const float *)w2)[(long)o * d_h + j];
             s = fmaf(w, a[j], s);
         }
-        s = wave_sum(s) + (b2 ? b2[o] : 0.f);
+        s = wave_sum(s);
+        if (lane == 0)
+            partial[wave * n_out + o] = s;
+    }
+    __syncthreads();
+    if (wave != 0)
+        return;
+    // online softmax-expectation over the n_out outputs (every lane carries the same values)
+    float m = -__builtin_inff(), den = 0.f, num = 0.f, y = 0.f;
+    for (int o = 0; o < n_out; ++o) {
+        const float s = ((partial[o] + partial[n_out + o]) + (partial[2 * n_out + o] + partial[3 * n_out + o])) +
+                        (b2 ? b2[o] : 0.f);
         if (n_out == 1) {
             y = s;
         } else {
@@ -204,17 +218,27 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
     if (a.B <= 0)
         return hipSuccess;
     const int nks = head_k_splits(a.d, a.d_h, a.B);
-    const size_t lds2 = (size_t)a.d_h * sizeof(float);
-    if (lds2 > 64 * 1024)
+    const size_t lds2 = ((size_t)a.d_h + 4 * (size_t)a.n_out) * sizeof(float);
+    if (lds2 > 96 * 1024)
         return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e1 = hipFuncSetAttribute((const void *)head_layer2_kernel<true>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipError_t e2 = hipFuncSetAttribute((const void *)head_layer2_kernel<false>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e1 != hipSuccess || e2 != hipSuccess)
+            return e1 != hipSuccess ? e1 : e2;
+        attr_set = true;
+    }
     hipError_t e = head_layer1(a.x, a.slot, a.B, a.d, a.d_h, a.w1, a.wdtype, a.act, st);
     if (e != hipSuccess)
         return e;
     if (a.wdtype == DT_BF16)
-        hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
+        hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(256), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
                            a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
     else
-        hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(64), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
+        hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(256), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
                            a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
     return hipGetLastError();
 }
