@@ -279,11 +279,12 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         __builtin_amdgcn_sched_barrier(0);                                                             \
     }
     // The next step's blocks have landed (own loads; the newest NSTAGE-2 steps may still be in
-    // flight), then everyone's; every read of the current stage has been issued and, being
-    // consumed by the MFMAs above, completed.  A bare barrier: a fence would drain the whole ring.
+    // flight) and this wave's reads of the current stage have returned; then everyone's.  After the
+    // barrier the current stage may be overwritten.  A bare barrier: a fence would drain the ring.
 #define EGTP_STEP_BARRIER()                                                                            \
     {                                                                                                  \
         wait_vmcnt<(NSTAGE - 2) * LOADS_PER_STEP>();                                                   \
+        __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0), the other counters unconstrained */         \
         __builtin_amdgcn_s_barrier();                                                                  \
         __builtin_amdgcn_sched_barrier(0);                                                             \
     }
