@@ -176,6 +176,58 @@ def test_k_bin_head_expected_value(gpu):
     assert_egtp_close(got, want)
 
 
+def test_head_maximum_sizes(gpu):
+    # widest head the interface takes: d_h = 16384 hidden units, K = 1024 bins, biases on both
+    # layers; bf16 and fp32 weight storage
+    K, d_h = 1024, 16384
+    w = _small_bf16(seed=47, B=3, d=64, V=300, d_h=d_h, lengths=(9, 1, 40))
+    rng = np.random.default_rng(2)
+    w2f = (rng.normal(0, 1.0, size=(K, d_h)) / np.sqrt(d_h)).astype(np.float32)
+    b1 = (0.05 * rng.normal(size=d_h)).astype(np.float32)
+    b2 = rng.normal(size=K).astype(np.float32)
+    centers = np.linspace(1.0, 8192.0, K).astype(np.float32)
+    off = oracle.offsets_from_lengths(w.lengths)
+    got = _run(gpu, w, w2=wl.to_bf16_bits(w2f), b1=b1, b2=b2, centers=centers)
+    head = oracle.Head(w.w1, wl.to_bf16_bits(w2f), b1, b2, centers.astype(np.float64))
+    assert_egtp_close(got, oracle.egtp(w.hidden, off, w.w_lm, head))
+    # fp32 storage of the same head
+    td = gpu.to_device
+    w1f = wl.bf16_bits_to_f32(w.w1)
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w1f), td(w2f), td(b1), td(b2), td(centers)))
+    out = _np(sc.score(td(w.hidden), _offsets_on_gpu(gpu, sc, w.lengths)))
+    head = oracle.Head(w1f, w2f, b1, b2, centers.astype(np.float64))
+    assert_egtp_close(out, oracle.egtp(w.hidden, off, w.w_lm, head))
+    sc.close()
+
+
+@pytest.mark.parametrize("B", [1, 63, 64, 65, 130])
+def test_head_batch_tile_boundaries(gpu, B):
+    # the first head layer works on 64-sequence tiles and slices d into more pieces the fewer tiles
+    # there are: batches around the tile boundaries, one token per sequence so that pooled = token
+    w = _small_bf16(seed=53 + B, B=B, d=320, V=257, d_h=72, lengths=tuple([1] * B))
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, np.arange(B + 1, dtype=np.int32), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+def test_many_token_blocks_few_vocabulary_tiles(gpu):
+    # 11 token blocks (one ragged group of 8 + 3) against 3 vocabulary tiles: the unit remap has to
+    # cope with a last group that is not full and with fewer vocabulary ranges than asked for
+    w = _small_bf16(seed=59, B=4, d=64, V=600, d_h=8, lengths=(700, 1100, 1, 900))
+    assert (w.T + 255) // 256 == 11
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+def test_large_hidden_size(gpu):
+    # d = 16384: 512 K steps per vocabulary tile through the ring; small T and V keep the oracle quick
+    w = _small_bf16(seed=61, B=2, d=16384, V=300, d_h=8, lengths=(3, 70))
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, [0, 3, 73], w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
 def test_deterministic_and_batch_invariant(gpu):
     w = _small_bf16(seed=19, B=5, d=256, V=1500, d_h=32)
     sc = _scorer(gpu, w)
