@@ -334,8 +334,10 @@ class HeadTrainer:
         need = egtp_head_train_workspace_bytes(B, self.d, self.d_h, self.K)
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
-        self.t += 1
-        egtp_head_train_step(self._struct(), x, bins, y, steps_per_seq, n_seqs, B, self._ws, self.loss)
+        h = self._struct()
+        h.t = self.t + 1
+        egtp_head_train_step(h, x, bins, y, steps_per_seq, n_seqs, B, self._ws, self.loss)
+        self.t += 1                      # only a step that was enqueued counts
         return self.loss
 
     def as_head(self) -> egtp_head:

@@ -579,11 +579,17 @@ egtp_status egtp_head_train_step(const egtp_head_train *h, const float *x, const
     if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 ||
         workspace_bytes < egtp_head_train_workspace_bytes(B, h->d, h->d_h, h->K))
         return EGTP_ERR_WORKSPACE;
+    // the architecture check is remembered per device: this call is made once per training step
+    static int arch_ok_device = -1;
     int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
-        strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    if (hipGetDevice(&dev) != hipSuccess)
         return EGTP_ERR_ARCH;
+    if (dev != arch_ok_device) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess || strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+            return EGTP_ERR_ARCH;
+        arch_ok_device = dev;
+    }
 
     const TrainWorkspace w = carve_train(workspace, B, h->d, h->d_h, h->K);
     TrainArgs a;
