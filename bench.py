@@ -131,7 +131,7 @@ def main() -> int:
     ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "train"],
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
-    ap.add_argument("--oracle-tokens", type=int, default=256, help="tokens of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
