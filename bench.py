@@ -23,12 +23,13 @@ HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E peak
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k1_entropy_bf16_serving_hbm_traffic.txt")
-K1_SOURCE = os.path.join(ROOT, "paper_2602_11812_amd", "csrc", "k1_entropy_bf16.hip")
+K1_SOURCES = [os.path.join(ROOT, "paper_2602_11812_amd", "csrc", f) for f in ("k1_entropy_bf16.hip", "k1_plan.cpp")]
 
 
 def recorded_traffic():
     """HBM bytes per launch of the fused kernel on the serving workload, from the committed rocprofv3
-    counter summary -- or None when there is none or the kernel source has changed since it was taken."""
+    counter summary -- or None when there is none or the kernel or its launch plan has changed since it was
+    taken."""
     import hashlib
     try:
         kv = {}
@@ -36,7 +37,7 @@ def recorded_traffic():
             if ":" in line and not line.startswith("#"):
                 k, v = line.split(":", 1)
                 kv[k.strip()] = v.strip()
-        sha = hashlib.sha256(open(K1_SOURCE, "rb").read()).hexdigest()
+        sha = hashlib.sha256(b"".join(open(f, "rb").read() for f in K1_SOURCES)).hexdigest()
         if kv.get("kernel_source_sha256") != sha:
             return None
         return float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"])

@@ -21,68 +21,6 @@ struct egtp_ctx {
     const void *w_packed;
 };
 
-namespace egtp {
-
-// ---- geometry of the fused entropy kernel ------------------------------------------------
-static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 8192;
-static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
-
-// compute units of the device the work is spread over (MI355X)
-static constexpr int NUM_CUS = 256;
-static constexpr int NSPLIT_SLACK = 8;  // how far above the minimum the number of ranges may go
-
-K1Plan k1_plan(int dtype, int64_t T, int /*d*/, int V)
-{
-    K1Plan p;
-    const bool bf = dtype == DT_BF16;
-    p.tb_tokens = bf ? BF16_TB : F32_TB;
-    p.tile_v = bf ? BF16_TV : F32_TV;
-    const int target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
-    p.ntb = (int)((T + p.tb_tokens - 1) / p.tb_tokens);
-    p.ntiles_v = (V + p.tile_v - 1) / p.tile_v;
-    int ns0 = p.ntb > 0 ? (target + p.ntb - 1) / p.ntb : 1;
-    if (ns0 < 1)
-        ns0 = 1;
-    // One workgroup per (token block, vocabulary range), one workgroup per compute unit at a
-    // time, all of about the same length: among the next few range counts take the one whose
-    // last round of workgroups is fullest.
-    double best = -1.0;
-    p.nsplit = 1;
-    p.tiles_per_split = p.ntiles_v;
-    for (int ns = ns0; ns <= ns0 + NSPLIT_SLACK; ++ns) {
-        const int nsc = ns > p.ntiles_v ? p.ntiles_v : ns;
-        const int tps = (p.ntiles_v + nsc - 1) / nsc;
-        const int nsplit = (p.ntiles_v + tps - 1) / tps;
-        const long units = (long)p.ntb * nsplit;
-        const long rounds = (units + NUM_CUS - 1) / NUM_CUS;
-        // time ~ rounds * tiles per range; work = ntb * ntiles_v tile sweeps on NUM_CUS units
-        const double fill = rounds > 0 ? (double)p.ntb * p.ntiles_v / ((double)rounds * tps * NUM_CUS) : 0.0;
-        if (fill > best + 1e-9) {
-            best = fill;
-            p.nsplit = nsplit;
-            p.tiles_per_split = tps;
-        }
-        if (nsc == p.ntiles_v)
-            break;
-    }
-    return p;
-}
-
-size_t k1_partial_floats(const K1Plan &p, int64_t T) { return (size_t)3 * (size_t)p.nsplit * (size_t)T; }
-
-size_t k1_partial_floats_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
-{
-    // nsplit(T') <= target / ntb(T') + 1 + NSPLIT_SLACK, so
-    // nsplit(T') * T' <= (target + (1 + NSPLIT_SLACK) * ntb(T')) * tb_tokens for every T' <= T
-    const bool bf = dtype == DT_BF16;
-    const int64_t tbk = bf ? BF16_TB : F32_TB;
-    const int64_t target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
-    const int64_t ntb = (T + tbk - 1) / tbk;
-    return (size_t)3 * (size_t)((target + (1 + NSPLIT_SLACK) * ntb) * tbk);
-}
-
-}  // namespace egtp
-
 using namespace egtp;
 
 namespace {
