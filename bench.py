@@ -133,6 +133,8 @@ def main() -> int:
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -200,6 +202,17 @@ def main() -> int:
 
     traffic = recorded_traffic()
 
+    # What the matrix cores of this device sustain with nothing else running (after the timed region):
+    # 6 launches of about 0.15 s each per operand kind, the mean of the last 4 reported.
+    probe = None
+    if not args.no_mfma_probe:
+        sink = torch.empty(gpu.egtp_mfma_probe_sink_floats(), dtype=torch.float32, device="cuda")
+        rnd = gpu.egtp_mfma_probe(sc.ctx, sink, 60000, True, 6)
+        zero = gpu.egtp_mfma_probe(sc.ctx, sink, 60000, False, 6)
+        probe = {"what": "register-only 16x16x32 bf16 MFMA loop, one wave per SIMD, 1024 workgroups",
+                 "random_operands_tflops": float(rnd[2:].mean()), "zero_operands_tflops": float(zero[2:].mean()),
+                 "achieved_over_random": achieved / float(rnd[2:].mean())}
+
     cpu = None
     if args.oracle_tokens > 0:
         import oracle
@@ -228,6 +241,7 @@ def main() -> int:
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": traffic if args.workload == "serving" else None,
                      "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
+        "mfma_probe": probe,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

@@ -215,6 +215,20 @@ egtp_status egtp_profile_enable(egtp_ctx *ctx, int on, int capacity);
  * Returns -1 on error. */
 int egtp_profile_read(egtp_ctx *ctx, float *ms_out_host, int cap);
 
+/* Measurement aid: the rate the matrix cores sustain on this device when nothing else runs --
+ * the reference the fused kernel's rate (Eq. 2 contraction) can be set against beside the
+ * published peak.  Launches `launches` (1..64) kernels back to back on `stream`; each runs, on
+ * 1024 workgroups of four waves, `iters` (1..10^7) steps of 64 bf16 MFMAs of the fused kernel's
+ * shape on registers only, with all-zero operands (random_operands == 0: clock-limited) or
+ * pseudo-random operands in [-1, 1) (power-limited).  Blocks until the last launch has ended.
+ *   sink          device, >= egtp_mfma_probe_sink_floats() floats, overwritten
+ *   tflops_out    host: [launches] achieved TFLOP/s of each launch (HIP events on `stream`)
+ * Creates and destroys its events inside the call; allocates no device memory. */
+size_t egtp_mfma_probe_sink_floats(void);
+egtp_status egtp_mfma_probe(egtp_ctx *ctx, float *sink, size_t sink_floats, int32_t iters,
+                            int32_t random_operands, int32_t launches, double *tflops_out_host,
+                            void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
-           "egtp_profile_enable", "egtp_profile_read", "egtp_packed_w_lm_bytes", "egtp_pack_w_lm",
+           "egtp_profile_enable", "egtp_profile_read", "egtp_mfma_probe_sink_floats", "egtp_mfma_probe",
+           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm",
            "egtp_head_train_workspace_bytes", "egtp_head_train_step", "egtp_sjf_order", "egtp_simulate_batches")
 
 
@@ -101,6 +102,10 @@ def load_library() -> ctypes.CDLL:
     lib.egtp_profile_enable.restype = c_int
     lib.egtp_profile_read.argtypes = [vp, vp, c_int]
     lib.egtp_profile_read.restype = c_int
+    lib.egtp_mfma_probe_sink_floats.argtypes = []
+    lib.egtp_mfma_probe_sink_floats.restype = c_size_t
+    lib.egtp_mfma_probe.argtypes = [vp, vp, c_size_t, i32, i32, i32, vp, vp]
+    lib.egtp_mfma_probe.restype = c_int
     lib.egtp_head_train_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.egtp_head_train_workspace_bytes.restype = c_size_t
     lib.egtp_head_train_step.argtypes = [POINTER(egtp_head_train), vp, vp, vp, vp, i32, i32, vp, c_size_t, vp, vp]
@@ -252,6 +257,22 @@ def egtp_profile_read(ctx, cap: int = 1024) -> np.ndarray:
     if n < 0:
         raise RuntimeError("egtp_profile_read failed")
     return buf[:n].copy()
+
+
+def egtp_mfma_probe_sink_floats() -> int:
+    return int(load_library().egtp_mfma_probe_sink_floats())
+
+
+def egtp_mfma_probe(ctx, sink: torch.Tensor, iters: int, random_operands: bool, launches: int,
+                    stream=None) -> np.ndarray:
+    """TFLOP/s of each of `launches` register-only MFMA kernels run back to back (blocks until done)."""
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.is_contiguous()
+    out = np.zeros(int(launches), dtype=np.float64)
+    st = load_library().egtp_mfma_probe(ctx, _dev(sink), sink.numel(), int(iters), int(bool(random_operands)),
+                                        int(launches), out.ctypes.data_as(c_void_p), _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_mfma_probe")
+    return out
 
 
 def egtp_head_train_workspace_bytes(B: int, d: int, d_h: int, K: int) -> int:

@@ -314,6 +314,43 @@ int egtp_profile_read(egtp_ctx *ctx, float *ms_out_host, int cap)
     return n;
 }
 
+size_t egtp_mfma_probe_sink_floats(void) { return (size_t)MFMA_PROBE_WORKGROUPS * 256; }
+
+egtp_status egtp_mfma_probe(egtp_ctx *ctx, float *sink, size_t sink_floats, int32_t iters,
+                            int32_t random_operands, int32_t launches, double *tflops_out_host,
+                            void *stream)
+{
+    if (!ctx || !sink || !tflops_out_host)
+        return EGTP_ERR_NULL;
+    if (iters < 1 || iters > 10000000 || launches < 1 || launches > 64)
+        return EGTP_ERR_SHAPE;
+    if (sink_floats < egtp_mfma_probe_sink_floats())
+        return EGTP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t ev[65] = {};
+    hipError_t e = hipSuccess;
+    for (int i = 0; i <= launches && e == hipSuccess; ++i)
+        e = hipEventCreate(&ev[i]);
+    if (e == hipSuccess)
+        e = hipEventRecord(ev[0], st);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) {
+        e = mfma_probe_launch(sink, iters, random_operands != 0, st);
+        if (e == hipSuccess)
+            e = hipEventRecord(ev[i + 1], st);
+    }
+    if (e == hipSuccess)
+        e = hipEventSynchronize(ev[launches]);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+        tflops_out_host[i] = ms > 0.f ? mfma_probe_flop(iters) / ((double)ms * 1e-3) / 1e12 : 0.0;
+    }
+    for (int i = 0; i <= launches; ++i)
+        if (ev[i])
+            (void)hipEventDestroy(ev[i]);
+    return e == hipSuccess ? EGTP_OK : hip_fail(ctx, e);
+}
+
 size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs)
 {
     if (!ctx || max_tokens < 0 || max_seqs < 0 || max_tokens > 0x7fffffffLL)

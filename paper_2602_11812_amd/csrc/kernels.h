@@ -130,4 +130,10 @@ struct TrainArgs {
 };
 hipError_t head_train_step(const TrainArgs &a, hipStream_t st);
 
+// Register-only MFMA loop (measurement aid): MFMA_PROBE_WORKGROUPS workgroups of 4 waves, each
+// wave `iters` steps of 64 MFMAs; sink holds one float per thread.
+constexpr int MFMA_PROBE_WORKGROUPS = 1024;
+double mfma_probe_flop(int iters);
+hipError_t mfma_probe_launch(float *sink, int iters, int random_operands, hipStream_t st);
+
 }  // namespace egtp

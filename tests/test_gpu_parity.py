@@ -390,3 +390,26 @@ def test_error_codes_before_any_launch(gpu):
     gpu.egtp_score(sc.ctx, hd, off, [0, 3, 7], 0, 0, None, None, None, None, None)               # B == 0: nothing to do
     gpu.egtp_score(sc.ctx, hd, off, [0, 3, 7], 2, 7, ws, *outs)                                  # and the good call works
     torch.cuda.synchronize()
+
+
+def test_mfma_probe_runs_and_checks_arguments(gpu):
+    """The measurement aid: rates are positive and below the chip's clock-limited ceiling; bad arguments
+    are turned into status codes before anything is launched."""
+    import torch
+    sc = _scorer(gpu, wl.make(wl.SPECS["tiny"]))
+    n = gpu.egtp_mfma_probe_sink_floats()
+    assert n == 1024 * 256
+    sink = torch.empty(n, dtype=torch.float32, device="cuda")
+    for random_operands in (False, True):
+        r = gpu.egtp_mfma_probe(sc.ctx, sink, 2000, random_operands, 2)
+        assert r.shape == (2,) and (r > 50.0).all() and (r < 2600.0).all(), r
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
+    assert float(gpu.egtp_mfma_probe(sc.ctx, sink, 1, False, 1)[0]) >= 0.0
+    for bad in (dict(iters=0), dict(launches=0), dict(launches=65)):
+        kw = dict(iters=10, launches=1)
+        kw.update(bad)
+        with pytest.raises(gpu.EgtpError):
+            gpu.egtp_mfma_probe(sc.ctx, sink, kw["iters"], False, kw["launches"])
+    with pytest.raises(gpu.EgtpError):
+        gpu.egtp_mfma_probe(sc.ctx, sink[:1000], 10, False, 1)
