@@ -45,6 +45,7 @@ struct Carver {
 struct Workspace {
     float *entropy;      // [T]
     float *k1_part;      // partial triples
+    int *k1_pace;        // pacing counters of the bf16 kernel
     int32_t *unit_start; // [B+1]
     float *lse_new;      // [B]
     float *state_scale;  // [B]
@@ -63,6 +64,7 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     const int dh = c.head_len.d_h > c.head_rem.d_h ? c.head_len.d_h : c.head_rem.d_h;
     w.entropy = cv.take<float>((size_t)T);
     w.k1_part = cv.take<float>(k1_partial_floats_bound(c.dtype, T, c.d, c.vocab));
+    w.k1_pace = cv.take<int>(k1_pace_ints_bound(c.dtype, T, c.d, c.vocab));
     w.unit_start = cv.take<int32_t>((size_t)B + 1);
     w.lse_new = cv.take<float>((size_t)B);
     w.state_scale = cv.take<float>((size_t)B);
@@ -135,7 +137,7 @@ egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Work
     if (timed)
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count], st));
     if (c.dtype == EGTP_BF16) {
-        EGTP_HIP(k1_entropy_bf16(w.hidden_packed, wp, T, c.d, c.vocab, p, w.k1_part, st));
+        EGTP_HIP(k1_entropy_bf16(w.hidden_packed, wp, T, c.d, c.vocab, p, w.k1_part, w.k1_pace, st));
     } else {
         EGTP_HIP(k1_entropy_f32(hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
     }

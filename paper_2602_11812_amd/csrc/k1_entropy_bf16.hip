@@ -29,6 +29,14 @@
 // per SIMD means nothing hides a stall, so the instruction order inside a K step is pinned:
 // loads and fragment reads are spread between the MFMAs, which cover them.  The one barrier
 // per step sits between the step's two halves, after the last read of the current stage.
+//
+// Pacing.  The 32 workgroups that run on one XCD at a time cover 8 token blocks x 4 vocabulary
+// ranges and read every block they share from the XCD's L2 -- as long as they walk through K
+// together.  Left alone they drift apart and the L2 (4 MiB, about 20 K steps of their blocks)
+// misses; the extra traffic over the fabric costs power, and power is the limit.  So every
+// PACE_TILES vocabulary tiles each workgroup counts itself in on a counter of its cohort and
+// the early ones wait for the rest.  The wait is a hint, not a dependency: it is bounded, a
+// workgroup whose wait runs out stops pacing for good, and no result depends on it.
 #include "kernels.h"
 
 namespace egtp {
@@ -47,6 +55,11 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // W block + hidden block
 constexpr int NPASS = TILE_BYTES / 4096;     // 16-byte loads per lane and operand block (4)
 constexpr int LOADS_PER_STEP = 2 * NPASS;
 constexpr int TB_GROUP = 8;    // token blocks that sweep the same vocabulary range together
+constexpr int XCDS = 8;            // workgroup i is placed on XCD i % 8
+constexpr int COHORT = 32;         // workgroups one XCD runs at a time (its compute units)
+constexpr int PACE_TILES = 4;      // vocabulary tiles between two pacing points
+constexpr int PACE_SPINS = 24;     // bound of one wait: polls of the counter ...
+constexpr int PACE_SLEEP = 4;      // ... each followed by a sleep of 64 * PACE_SLEEP cycles
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float LOG2E = 1.4426950408889634f;
 static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geometry");
@@ -141,10 +154,17 @@ __device__ __forceinline__ void fold16(const float (&zin)[16], Stats &st, int ro
     st.U += U0 + U1;
 }
 
+__global__ void k1_pace_zero_kernel(int *__restrict__ pace, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n)
+        pace[i] = 0;
+}
+
 template <int NSTAGE>
 __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     const unsigned char *__restrict__ Wp, const unsigned char *__restrict__ Hp, long T, int KT, int V,
-    int ntb, int nsplit, int tps, int ntiles_v, float *__restrict__ part)
+    int ntb, int nsplit, int tps, int ntiles_v, float *__restrict__ part, int *__restrict__ pace)
 {
     static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LOADS_PER_STEP < 64, "ring depth");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -159,11 +179,19 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
     // logical units so that neighbours in time share W_lm blocks and token blocks in its L2.
     int tb, sp;
+    int *pace_cnt = nullptr;  // this workgroup's cohort counter (thread 0 only), or NULL: no pacing
+    int pace_members = 0;
     {
         const int units = gridDim.x;
         const int id = blockIdx.x;
         const int q = units >> 3, r = units & 7;
         const int x = id & 7, j = id >> 3;
+        // cohort = 32 consecutive workgroups of one XCD (the ones it starts together)
+        if (pace != nullptr && tid == 0) {
+            const int cohort = j / COHORT;
+            pace_cnt = pace + x * k1_pace_cohorts(units) + cohort;
+            pace_members = min(COHORT, q + (x < r ? 1 : 0) - cohort * COHORT);
+        }
         const int logical = x * q + (x < r ? x : r) + j;
         const int per_group = TB_GROUP * nsplit;
         const int g = logical / per_group;
@@ -331,6 +359,13 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
         EGTP_STEP_BARRIER();
         EGTP_HALF1(fbB, fbA);
 
+        // pacing point: count in now, look at the counter after the fold (the round trip to the
+        // L2 is hidden behind it)
+        const int tiles_done = vt - vt_begin + 1;
+        const bool pace_now = pace_cnt != nullptr && tiles_done % PACE_TILES == 0 && tiles_done < tps;
+        if (pace_now)
+            __hip_atomic_fetch_add(pace_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
         // a full tile of logits is in registers: fold it into the statistics and forget it
         const int row_base = vt * BM + wm * 128 + 4 * kq;
         const bool masked = vt * BM + BM > V;
@@ -352,6 +387,23 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
                     fold16<false>(z, st[ni], row_base + h * 64, V);
             }
         }
+        if (pace_now) {
+            // the other waves wait for this thread at the next step barrier
+            const int want = pace_members * (tiles_done / PACE_TILES);
+            bool met = false;
+            for (int spin = 0; spin < PACE_SPINS && !met; ++spin) {
+                met = __hip_atomic_load(pace_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want;
+                if (!met)
+                    __builtin_amdgcn_s_sleep(PACE_SLEEP);
+            }
+            if (!met) {
+                // the cohort is not running together: count in for every later point and stop
+                const int later = (tps - 1) / PACE_TILES - tiles_done / PACE_TILES;
+                if (later > 0)
+                    __hip_atomic_fetch_add(pace_cnt, later, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pace_cnt = nullptr;
+            }
+        }
         if (vt + 1 < vt_end)
             EGTP_HALF0(fbA);  // first half of the next tile's first step
     }
@@ -359,6 +411,13 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
 #undef EGTP_HALF1
 #undef EGTP_STEP_BARRIER
 
+    if (pace_cnt != nullptr) {
+        // a range with fewer tiles than the others leaves early: count in for the points it skips
+        const int mine = vt_end - vt_begin;
+        const int skipped = (tps - 1) / PACE_TILES - (mine < tps ? mine / PACE_TILES : (tps - 1) / PACE_TILES);
+        if (skipped > 0)
+            __hip_atomic_fetch_add(pace_cnt, skipped, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -512,7 +571,7 @@ hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hi
 }
 
 hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
-                           const K1Plan &p, float *part, hipStream_t st)
+                           const K1Plan &p, float *part, int *pace, hipStream_t st)
 {
     constexpr int NSTAGE = 4;
     constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
@@ -530,9 +589,16 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
     const int kt = k_steps(d);
+    // pacing counters: one per cohort, cleared by a kernel (a caller may be capturing a graph)
+    if (p.tiles_per_split <= PACE_TILES)
+        pace = nullptr;  // no pacing point inside a range
+    if (pace != nullptr) {
+        const int n = XCDS * k1_pace_cohorts(units);
+        hipLaunchKernelGGL(k1_pace_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, pace, n);
+    }
     hipLaunchKernelGGL((k1_entropy_bf16_kernel<NSTAGE>), dim3((unsigned)units), dim3(256), LDS_BYTES, st,
                        (const unsigned char *)w_packed, (const unsigned char *)hidden_packed, (long)T, kt, V,
-                       p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part);
+                       p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part, pace);
     return hipGetLastError();
 }
 

@@ -65,4 +65,14 @@ size_t k1_partial_floats_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
     return (size_t)3 * (size_t)((target + (1 + NSPLIT_SLACK) * ntb) * tbk);
 }
 
+size_t k1_pace_ints_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
+{
+    // units(T') = ntb(T') * nsplit(T') <= target + (1 + NSPLIT_SLACK) * ntb(T)
+    const bool bf = dtype == DT_BF16;
+    const int64_t tbk = bf ? BF16_TB : F32_TB;
+    const int64_t target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const int64_t ntb = (T + tbk - 1) / tbk;
+    return (size_t)8 * (size_t)k1_pace_cohorts((long)(target + (1 + NSPLIT_SLACK) * ntb));
+}
+
 }  // namespace egtp

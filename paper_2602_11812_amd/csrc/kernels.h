@@ -27,6 +27,10 @@ K1Plan k1_plan(int dtype, int64_t T, int d, int V);
 size_t k1_partial_floats(const K1Plan &p, int64_t T);
 // upper bound of k1_partial_floats over every T' <= T
 size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
+// The bf16 kernel paces the workgroups that share an XCD with one counter per cohort of 32:
+// cohorts per XCD for a grid of `units` workgroups, and ints to reserve for every T' <= T.
+__host__ __device__ inline int k1_pace_cohorts(long units) { return (int)(((units + 7) / 8 + 31) / 32); }
+size_t k1_pace_ints_bound(int dtype, int64_t T, int d, int V);
 
 // Packed operand layout of the bf16 matrix-core kernel: blocks of 256 rows x K1_PACK_K
 // elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * steps + step with
@@ -38,9 +42,10 @@ size_t k1_packed_bytes(int64_t rows, int d);
 hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hipStream_t st);
 
 // Eq. 2, fused: partial (max, sum e^{z-m}, sum e^{z-m}(z-m) log2 e) per token and vocabulary range.
-// bf16: both operands in the packed layout.
+// bf16: both operands in the packed layout; `pace`: k1_pace_ints_bound ints of scratch (contents
+// do not matter on entry), or NULL to run without pacing.
 hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
-                           const K1Plan &p, float *part, hipStream_t st);
+                           const K1Plan &p, float *part, int *pace, hipStream_t st);
 // fp32 inputs (row-major), plain fp32 FMAs
 hipError_t k1_entropy_f32(const void *hidden, const void *w_lm, int64_t T, int d, int V,
                           const K1Plan &p, float *part, hipStream_t st);
