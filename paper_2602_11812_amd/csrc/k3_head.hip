@@ -2,11 +2,18 @@
 // either the scalar itself (n_out == 1) or the expected value over K bins of Eq. 6.
 //
 // Layer 1 is a small [B x d] . [d x d_h] contraction kept entirely in fp32 (the pooled
-// vector is never re-rounded); it is LDS-tiled, 64 x 64 outputs per workgroup, 4 x 4 per
-// thread, and split along d (blockIdx.z) so that about a thousand workgroups exist even for one
+// vector is never re-rounded); the plain kernel is LDS-tiled, 64 x 64 outputs per workgroup, 4 x 4
+// per thread.  The contraction is split along d so that about a thousand workgroups exist even for one
 // small batch; the splits leave partial pre-activations that layer 2 adds in split order
 // (fixed order, bit-reproducible) before bias and ReLU.  Layer 2 and the K-bin decode are one
 // workgroup per sequence.
+//
+// With bf16 weights and d a multiple of 8, layer 1 runs on the bf16 matrix cores without
+// rounding the pooled vector: an fp32 value is the exact sum of three bf16 values (its top 8
+// significant bits, the top 8 of what is left, and the rest), a bf16 x bf16 product is exact in
+// fp32, so three MFMAs per weight fragment accumulate the same products an fp32 dot product
+// would, in fp32.  Fragments come straight from global memory: a lane's 8 K-elements are 16
+// contiguous bytes of a weight row and 32 contiguous bytes of a pooled row.
 #include "kernels.h"
 
 namespace egtp {
@@ -95,6 +102,184 @@ __global__ __launch_bounds__(256) void head_layer1_kernel(const float *__restric
             const int jj = j0 + tx * 4 + i;
             if (jj < d_h)
                 act[(long)s * d_h + jj] = acc[i][j];
+        }
+    }
+}
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int MK = 32;  // K elements per MFMA step
+
+// 8 fp32 values -> three bf16 fragments whose sum is exactly the input (truncating splits)
+__device__ __forceinline__ void split3(const float (&f)[8], bf16x8 &hi, bf16x8 &mid, bf16x8 &lo)
+{
+    unsigned h[8], m[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        h[i] = __float_as_uint(f[i]) & 0xffff0000u;
+        const float r1 = f[i] - __uint_as_float(h[i]);
+        m[i] = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(m[i]);
+        l[i] = __float_as_uint(r2) & 0xffff0000u;
+    }
+    u32x4 ph, pm, pl;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ph[i] = (h[2 * i] >> 16) | h[2 * i + 1];
+        pm[i] = (m[2 * i] >> 16) | m[2 * i + 1];
+        pl[i] = (l[2 * i] >> 16) | l[2 * i + 1];
+    }
+    hi = __builtin_bit_cast(bf16x8, ph);
+    mid = __builtin_bit_cast(bf16x8, pm);
+    lo = __builtin_bit_cast(bf16x8, pl);
+}
+
+// Layer 1 on the matrix cores, bf16 weights, d % 8 == 0.  Workgroup = 4 waves, MJ = 128 head rows x
+// TN = 64 sequences; wave = 64 x 32 = 4 x 2 MFMA 16x16x32 tiles, weights as the row operand (lane l:
+// head row l % 16, K elements 8 * (l / 16) .. + 8), pooled vectors as the column operand; in the
+// accumulator a lane holds head rows 4 * (l / 16) + i of sequence l % 16.  Per K step every thread
+// fetches 8 K-elements of one pooled row (32 bytes) and of two weight rows (16 bytes each), splits
+// the fp32 values once, and leaves all of it in LDS in fragment order -- fragment f, lane l at
+// (f * 64 + l) * 16 bytes -- so that a fragment read is one linear 16-byte read per lane.  Two
+// LDS buffers; global fetches run three steps ahead in registers.
+constexpr int MJ = 128;
+constexpr int MFMA_W_FRAGS = MJ / 16;             // 8 weight fragments per step
+constexpr int MFMA_X_FRAGS = 3 * (TN / 16);       // 3 parts x 4 sequence fragments
+constexpr int MFMA_STAGE_BYTES = (MFMA_W_FRAGS + MFMA_X_FRAGS) * 1024;
+
+__global__ __launch_bounds__(256) void head_layer1_mfma_kernel(const float *__restrict__ x,
+                                                               const int32_t *__restrict__ slot, int B, int d,
+                                                               int d_h, const unsigned short *__restrict__ w1,
+                                                               int kchunk, int nks, int jtiles,
+                                                               float *__restrict__ act_part)
+{
+    __shared__ __align__(16) unsigned char lds[2 * MFMA_STAGE_BYTES];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l15 = lane & 15, kq = lane >> 4;
+    // Workgroup i runs on XCD i % 8: the slice along d varies fastest, so that an XCD's L2 only
+    // ever pulls its own slices of the weights and of the pooled vectors over the fabric.
+    const int kslice = blockIdx.x % nks;
+    const int tile = blockIdx.x / nks;
+    const int j0 = (tile % jtiles) * MJ, s0 = (tile / jtiles) * TN;
+    const int wj = (wave & 1) * 4;  // first of this wave's 4 weight fragments
+    const int ws = (wave >> 1) * 2; // first of its 2 sequence fragments
+
+    // what this thread stages: row 16 * wave + lane % 16 of the tile (and that row + 64 of the
+    // weights), K elements 8 * (lane / 16) .. + 8 -- which is lane `lane` of fragment `wave`, so a
+    // wave's 16-byte LDS writes are one linear KiB
+    const int srow_l = wave * 16 + l15, kpart = kq;
+    int srow = s0 + srow_l;
+    srow = srow < B ? srow : B - 1;  // clamped rows are computed and dropped
+    const long xrow = slot ? slot[srow] : srow;
+    const float *xp = x + xrow * (long)d + 8 * kpart;
+    const unsigned short *wp[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        int jrow = j0 + 64 * r + srow_l;
+        jrow = jrow < d_h ? jrow : d_h - 1;
+        wp[r] = w1 + (long)jrow * d + 8 * kpart;
+    }
+    const unsigned stage_lane = (unsigned)(lane * 16);
+    const unsigned w_dst0 = (unsigned)(wave * 1024) + stage_lane;                   // rows 0..63
+    const unsigned w_dst1 = (unsigned)((4 + wave) * 1024) + stage_lane;             // rows 64..127
+    const unsigned x_dst = (unsigned)((MFMA_W_FRAGS + wave) * 1024) + stage_lane;   // part p: + p * 4096
+
+    f32x4 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int kbeg = kslice * kchunk;
+    const int kend = min(d, kbeg + kchunk);
+    // kend and 8 * kpart are multiples of 8: a thread's 8 elements are inside [kbeg, kend) or all outside
+    struct Fetched {
+        u32x4 w[2];
+        float4 x[2];
+    };
+    auto fetch = [&](int k0, Fetched &r) {
+        r.w[0] = r.w[1] = u32x4{0u, 0u, 0u, 0u};
+        r.x[0] = r.x[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 + 8 * kpart < kend) {
+            r.w[0] = *(const u32x4 *)(wp[0] + k0);
+            r.w[1] = *(const u32x4 *)(wp[1] + k0);
+            r.x[0] = *(const float4 *)(xp + k0);
+            r.x[1] = *(const float4 *)(xp + k0 + 4);
+        }
+    };
+    auto stage = [&](const Fetched &r, unsigned char *buf) {
+        const float f[8] = {r.x[0].x, r.x[0].y, r.x[0].z, r.x[0].w, r.x[1].x, r.x[1].y, r.x[1].z, r.x[1].w};
+        bf16x8 hi, mid, lo;
+        split3(f, hi, mid, lo);
+        *(u32x4 *)(buf + w_dst0) = r.w[0];
+        *(u32x4 *)(buf + w_dst1) = r.w[1];
+        *(bf16x8 *)(buf + x_dst) = hi;
+        *(bf16x8 *)(buf + x_dst + 4096) = mid;
+        *(bf16x8 *)(buf + x_dst + 8192) = lo;
+    };
+
+    // Operands are fetched three steps ahead into a ring of three register sets (the loop is
+    // unrolled by three so that the ring is indexed statically) and staged one step ahead.
+    Fetched ring[3];
+    fetch(kbeg, ring[0]);
+    fetch(kbeg + MK, ring[1]);
+    fetch(kbeg + 2 * MK, ring[2]);
+    stage(ring[0], lds);
+    __syncthreads();
+    int cur = 0;
+    for (int base = kbeg; base < kend; base += 3 * MK) {
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int k0 = base + u * MK;
+            if (k0 >= kend)
+                break;
+            fetch(k0 + 3 * MK, ring[u]);  // ring[u] held step k0, which is in LDS already
+            const unsigned char *buf = lds + cur * MFMA_STAGE_BYTES;
+            bf16x8 wf[4], xf[3][2];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                wf[a] = *(const bf16x8 *)(buf + ((wj + a) * 64 + lane) * 16);
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    xf[p][b] = *(const bf16x8 *)(buf + ((MFMA_W_FRAGS + 4 * p + ws + b) * 64 + lane) * 16);
+#pragma unroll
+            for (int p = 2; p >= 0; --p)  // smallest parts first
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[a], xf[p][b], acc[a][b], 0, 0, 0);
+            if (k0 + MK < kend)
+                stage(ring[(u + 1) % 3], lds + (cur ^ 1) * MFMA_STAGE_BYTES);  // nobody reads that buffer now
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    float *act = act_part + (long)kslice * B * d_h;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int s = s0 + 16 * (ws + b) + l15;
+        if (s >= B)
+            continue;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int jj = j0 + 16 * (wj + a) + 4 * kq;
+            if (jj + 3 < d_h && (d_h & 3) == 0) {
+                *(f32x4 *)(act + (long)s * d_h + jj) = acc[a][b];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (jj + i < d_h)
+                        act[(long)s * d_h + jj + i] = acc[a][b][i];
+            }
         }
     }
 }
@@ -202,8 +387,20 @@ hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, in
     if (B <= 0)
         return hipSuccess;
     const int nks = head_k_splits(d, d_h, B);
-    const int kchunk = ((d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
     const dim3 grid((d_h + TM - 1) / TM, (B + TN - 1) / TN, nks);
+    if (wdtype == DT_BF16 && d % 8 == 0) {
+        // matrix-core path: slices are multiples of the MFMA K step (late slices may be empty
+        // and then write zeros)
+        const int kchunk_m = ((d + nks - 1) / nks + MK - 1) / MK * MK;
+        const int jtiles = (d_h + MJ - 1) / MJ;
+        const long wgs = (long)jtiles * ((B + TN - 1) / TN) * nks;
+        if (wgs > 0x7fffffffL)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(head_layer1_mfma_kernel, dim3((unsigned)wgs), dim3(256), 0, st, x, slot, B, d, d_h,
+                           (const unsigned short *)w1, kchunk_m, nks, jtiles, act_part);
+        return hipGetLastError();
+    }
+    const int kchunk = ((d + nks - 1) / nks + TK - 1) / TK * TK;  // multiple of the K step
     if (wdtype == DT_BF16)
         hipLaunchKernelGGL(head_layer1_kernel<true>, grid, dim3(256), 0, st, x, slot, B, d, d_h, w1, kchunk,
                            act_part);
