@@ -413,3 +413,23 @@ def test_mfma_probe_runs_and_checks_arguments(gpu):
             gpu.egtp_mfma_probe(sc.ctx, sink, kw["iters"], False, kw["launches"])
     with pytest.raises(gpu.EgtpError):
         gpu.egtp_mfma_probe(sc.ctx, sink[:1000], 10, False, 1)
+
+
+def test_head_keeps_the_pooled_vector_in_fp32(gpu):
+    """The head must not re-round its fp32 input to bf16 on its way to the matrix cores: against the
+    oracle's head evaluated in fp64 on the GPU's own pooled vectors, predictions agree to fp32
+    accumulation noise, and the same head on inputs cut to one bf16 piece misses that bar."""
+    w = wl.make(wl.SPECS["mid"])
+    got = _run(gpu, w)
+    pooled = got["pooled"].astype(np.float64)
+    head = oracle.Head(w.w1, w.w2)
+    want = oracle.predict(pooled, head)
+    # scale of the sum each prediction is: sum_j |w2_j| * sum_k |W1_jk x_k|
+    w1 = wl.bf16_bits_to_f32(w.w1).astype(np.float64)
+    w2 = wl.bf16_bits_to_f32(w.w2).astype(np.float64)
+    scale = (np.abs(pooled) @ np.abs(w1).T) @ np.abs(w2).reshape(-1)
+    err = np.abs(got["pred"].astype(np.float64) - want) / scale
+    bar = 1e-6
+    assert err.max() < bar, err.max()
+    hi = (got["pooled"].view(np.uint32) & np.uint32(0xffff0000)).view(np.float32).astype(np.float64)
+    assert (np.abs(oracle.predict(hi, head) - want) / scale).max() > 2 * bar
