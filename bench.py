@@ -23,7 +23,7 @@ HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E peak
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k1_entropy_bf16_serving_hbm_traffic.txt")
-K1_SOURCES = [os.path.join(ROOT, "paper_2602_11812_amd", "csrc", f) for f in ("k1_entropy_bf16.hip", "k1_plan.cpp")]
+K1_SOURCES = [os.path.join(ROOT, "paper_2602_11812_amd", "csrc", f) for f in ("k1_entropy_bf16.hip", "k1_common.h", "k1_plan.cpp")]
 
 
 def recorded_traffic():

@@ -37,7 +37,7 @@
 // PACE_TILES vocabulary tiles each workgroup counts itself in on a counter of its cohort and
 // the early ones wait for the rest.  The wait is a hint, not a dependency: it is bounded, a
 // workgroup whose wait runs out stops pacing for good, and no result depends on it.
-#include "kernels.h"
+#include "k1_common.h"
 
 namespace egtp {
 
@@ -48,9 +48,6 @@ namespace {
 
 constexpr int BM = 256;        // vocabulary rows per tile
 constexpr int BN = 256;        // tokens per block
-constexpr int BK = K1_PACK_K;  // K elements per step (32)
-constexpr int ROW_BYTES = BK * 2;
-constexpr int TILE_BYTES = 256 * ROW_BYTES;  // one operand block, 16 KiB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // W block + hidden block
 constexpr int NPASS = TILE_BYTES / 4096;     // 16-byte loads per lane and operand block (4)
 constexpr int LOADS_PER_STEP = 2 * NPASS;
@@ -60,39 +57,6 @@ constexpr int COHORT = 32;         // workgroups one XCD runs at a time (its com
 constexpr int PACE_TILES = 4;      // vocabulary tiles between two pacing points
 constexpr int PACE_SPINS = 24;     // bound of one wait: polls of the counter ...
 constexpr int PACE_SLEEP = 4;      // ... each followed by a sleep of 64 * PACE_SLEEP cycles
-constexpr float NEG_BIG = -1.0e30f;
-constexpr float LOG2E = 1.4426950408889634f;
-static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geometry");
-
-struct Stats {
-    float m, S, U;
-};
-
-// K steps of a sweep over d: K is zero-padded to a multiple of two steps, so that the main loop
-// can be unrolled by two (the fragment registers swap roles every step).
-__host__ __device__ __forceinline__ int k_steps(int d) { return 2 * ((d + 2 * BK - 1) / (2 * BK)); }
-
-// XOR key of a row's four 16-byte chunks inside a packed block (64-byte rows).  With the
-// fragment layout below (lane l reads row l%16 + 16t, chunk l/16) this key makes the 16-byte-per-
-// lane LDS reads as fast as a linear read; found by timing candidate keys on the hardware (most
-// others, the identity included, cost a third more LDS cycles per read).
-__host__ __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & 3; }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// (m1,S1,U1) (+) (m2,S2,U2): statistics of the union of two disjoint sets of logits
-__device__ __forceinline__ Stats merge(Stats a, Stats b)
-{
-    float M = fmaxf(a.m, b.m);
-    float da = (a.m - M) * LOG2E, db = (b.m - M) * LOG2E;
-    float sa = fast_exp2(da), sb = fast_exp2(db);
-    Stats r;
-    r.m = M;
-    r.S = a.S * sa + b.S * sb;
-    r.U = (a.U + da * a.S) * sa + (b.U + db * b.S) * sb;
-    return r;
-}
-
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
 // [3:0] and [15:14], export and LDS/scalar counters left at their maxima)
 template <int N>
@@ -465,110 +429,7 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     }
 }
 
-// entropy[t] from the nsplit partial triples of token t, merged in range order
-__global__ __launch_bounds__(256) void k1_merge_kernel(const float *__restrict__ part, int nsplit,
-                                                       long T, float *__restrict__ entropy)
-{
-    const long t = (long)blockIdx.x * 256 + threadIdx.x;
-    if (t >= T)
-        return;
-    const long plane = (long)nsplit * T;
-    Stats a;
-    a.m = part[t];
-    a.S = part[plane + t];
-    a.U = part[2 * plane + t];
-    for (int s = 1; s < nsplit; ++s) {
-        Stats b;
-        const long idx = (long)s * T + t;
-        b.m = part[idx];
-        b.S = part[plane + idx];
-        b.U = part[2 * plane + idx];
-        a = merge(a, b);
-    }
-    entropy[t] = logf(a.S) - a.U * 0.6931471805599453f / a.S;
-}
-
-// The same merge for many ranges per token (small batches split the vocabulary finely): one
-// wave per token, lane l takes ranges l, l+64, ... in order, then a fixed xor tree joins the
-// lanes -- still a fixed order, so bit-reproducible.
-__global__ __launch_bounds__(256) void k1_merge_wide_kernel(const float *__restrict__ part, int nsplit,
-                                                            long T, float *__restrict__ entropy)
-{
-    const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (t >= T)
-        return;
-    const long plane = (long)nsplit * T;
-    Stats a;
-    a.m = NEG_BIG;
-    a.S = 0.f;
-    a.U = 0.f;
-    for (int s = lane; s < nsplit; s += 64) {
-        Stats b;
-        const long idx = (long)s * T + t;
-        b.m = part[idx];
-        b.S = part[plane + idx];
-        b.U = part[2 * plane + idx];
-        a = merge(a, b);
-    }
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        Stats b;
-        b.m = __shfl_xor(a.m, o);
-        b.S = __shfl_xor(a.S, o);
-        b.U = __shfl_xor(a.U, o);
-        a = merge(a, b);
-    }
-    if (lane == 0)
-        entropy[t] = logf(a.S) - a.U * 0.6931471805599453f / a.S;
-}
-
-// Packs rows of a row-major bf16 matrix src[R x d] into blocks of 256 rows x 32 K-elements in
-// LDS-image order; rows >= R and K >= d are zero.  One workgroup packs 8 consecutive K steps
-// of one row tile: a wave reads 512 contiguous bytes of each of two rows at a time.
-__global__ __launch_bounds__(256) void pack_rows_bf16_kernel(const unsigned char *__restrict__ src, long R,
-                                                             int d, int KT, unsigned char *__restrict__ dst)
-{
-    const long tile = blockIdx.x;
-    const int ks0 = blockIdx.y * 8;
-    const int c32 = threadIdx.x & 31;   // 16-byte chunk of the 512-byte span: K step c32/4, chunk c32%4
-    const int rsub = threadIdx.x >> 5;  // 8 rows per pass
-    const int ks = ks0 + (c32 >> 2);
-    const int chunk = c32 & 3;
-    const long k_elem = (long)ks * BK + chunk * 8;
-    if (ks >= KT)
-        return;
-    unsigned char *blk = dst + (tile * KT + ks) * (long)TILE_BYTES;
-    for (int r = rsub; r < 256; r += 8) {
-        const long row = tile * 256 + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row < R && k_elem < d)
-            v = *(const uint4 *)(src + (row * d + k_elem) * 2);
-        *(uint4 *)(blk + r * ROW_BYTES + ((chunk ^ swizzle_key(r)) << 4)) = v;
-    }
-}
-
 }  // namespace
-
-size_t k1_packed_bytes(int64_t rows, int d)
-{
-    const int64_t tiles = (rows + 255) / 256;
-    const int64_t kt = k_steps(d);
-    return (size_t)(tiles * kt) * TILE_BYTES;
-}
-
-hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hipStream_t st)
-{
-    if (rows <= 0)
-        return hipSuccess;
-    const long tiles = (rows + 255) / 256;
-    const int kt = k_steps(d);
-    if (tiles > 0x7fffffffL)
-        return hipErrorInvalidValue;
-    hipLaunchKernelGGL(pack_rows_bf16_kernel, dim3((unsigned)tiles, (kt + 7) / 8), dim3(256), 0, st,
-                       (const unsigned char *)src, (long)rows, d, kt, (unsigned char *)dst);
-    return hipGetLastError();
-}
 
 hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
                            const K1Plan &p, float *part, int *pace, hipStream_t st)
@@ -599,24 +460,6 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
     hipLaunchKernelGGL((k1_entropy_bf16_kernel<NSTAGE>), dim3((unsigned)units), dim3(256), LDS_BYTES, st,
                        (const unsigned char *)w_packed, (const unsigned char *)hidden_packed, (long)T, kt, V,
                        p.ntb, p.nsplit, p.tiles_per_split, p.ntiles_v, part, pace);
-    return hipGetLastError();
-}
-
-hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st)
-{
-    if (nsplit >= 32) {
-        const long wblocks = (T + 3) / 4;
-        if (wblocks <= 0 || wblocks > 0x7fffffffL)
-            return hipErrorInvalidValue;
-        hipLaunchKernelGGL(k1_merge_wide_kernel, dim3((unsigned)wblocks), dim3(256), 0, st, part, nsplit, (long)T,
-                           entropy);
-        return hipGetLastError();
-    }
-    const long blocks = (T + 255) / 256;
-    if (blocks <= 0 || blocks > 0x7fffffffL)
-        return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k1_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, nsplit,
-                       (long)T, entropy);
     return hipGetLastError();
 }
 
