@@ -436,14 +436,10 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
 {
     constexpr int NSTAGE = 4;
     constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k1_entropy_bf16_kernel<NSTAGE>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static unsigned long long lds_limit_raised = 0;
+    hipError_t ea = raise_dynamic_lds_limit((const void *)k1_entropy_bf16_kernel<NSTAGE>, LDS_BYTES, lds_limit_raised);
+    if (ea != hipSuccess)
+        return ea;
     if (p.tb_tokens != BN || p.tile_v != BM || T <= 0)
         return hipErrorInvalidValue;
     const long units = (long)p.ntb * p.nsplit;

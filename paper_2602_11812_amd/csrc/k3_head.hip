@@ -418,16 +418,11 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
     const size_t lds2 = ((size_t)a.d_h + 4 * (size_t)a.n_out) * sizeof(float);
     if (lds2 > 96 * 1024)
         return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e1 = hipFuncSetAttribute((const void *)head_layer2_kernel<true>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        hipError_t e2 = hipFuncSetAttribute((const void *)head_layer2_kernel<false>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e1 != hipSuccess || e2 != hipSuccess)
-            return e1 != hipSuccess ? e1 : e2;
-        attr_set = true;
-    }
+    static unsigned long long raised_bf16 = 0, raised_f32 = 0;
+    hipError_t e1 = raise_dynamic_lds_limit((const void *)head_layer2_kernel<true>, 96 * 1024, raised_bf16);
+    hipError_t e2 = raise_dynamic_lds_limit((const void *)head_layer2_kernel<false>, 96 * 1024, raised_f32);
+    if (e1 != hipSuccess || e2 != hipSuccess)
+        return e1 != hipSuccess ? e1 : e2;
     hipError_t e = head_layer1(a.x, a.slot, a.B, a.d, a.d_h, a.w1, a.wdtype, a.act, st);
     if (e != hipSuccess)
         return e;

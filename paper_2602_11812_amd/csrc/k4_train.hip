@@ -291,14 +291,10 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     const size_t lds = ((size_t)a.d_h + 2 * (size_t)a.K) * sizeof(float);
     if (lds > 96 * 1024)
         return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)train_sample_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static unsigned long long lds_limit_raised = 0;
+    hipError_t ea = raise_dynamic_lds_limit((const void *)train_sample_kernel, 96 * 1024, lds_limit_raised);
+    if (ea != hipSuccess)
+        return ea;
     hipError_t e = head_layer1(a.x, nullptr, a.B, a.d, a.d_h, a.w1, DT_F32, a.act_part, st);
     if (e != hipSuccess)
         return e;

@@ -6,6 +6,22 @@
 
 namespace egtp {
 
+// Raises a kernel's dynamic LDS limit once per device: `done` is the caller's bit mask of the
+// devices it has been raised on (a race between two first calls only repeats the setting).
+inline hipError_t raise_dynamic_lds_limit(const void *kernel, int bytes, unsigned long long &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev >= 0 && dev < 64 && ((done >> dev) & 1ull))
+        return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64)
+        done |= 1ull << dev;
+    return e;
+}
+
 // Storage types of hidden states / weights (values match the public enum).
 enum : int { DT_F32 = 0, DT_BF16 = 1 };
 
