@@ -229,7 +229,7 @@ def main() -> int:
                          f"{cdt:.1f}s"}
 
     line = {
-        "metric": "tokens scored/sec (EGTP prefill, d=4096 V=151936) + % bf16 MFMA peak",
+        "metric": f"tokens scored/sec (EGTP prefill, d={spec.d} V={spec.V}) + % bf16 MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

@@ -512,11 +512,11 @@ egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t 
         return s;
     hipStream_t st = (hipStream_t)stream;
     const egtp_config &c = ctx->cfg;
-    EGTP_HIP(pool_plain(hidden, c.dtype, c.d, offsets_dev, B, (int)kind, pooled_out, st));
-    if (pred_out) {
-        const Workspace w = carve(ctx, workspace, T, B);
+    const Workspace w = carve(ctx, workspace, T, B);
+    EGTP_HIP(pool_plain(hidden, c.dtype, c.d, offsets_dev, B, T, (int)kind, w.unit_start, w.pool_part, pooled_out,
+                        st));
+    if (pred_out)
         return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
-    }
     return EGTP_OK;
 }
 

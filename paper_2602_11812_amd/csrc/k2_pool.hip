@@ -148,7 +148,29 @@ __global__ __launch_bounds__(256) void pool_lse_kernel(const float *__restrict__
 }
 
 // ---- Eq. 4: partial weighted sums per unit --------------------------------------------------
+// MODE 0: weights e^{H/alpha - lse} (Eq. 3-4); MODE 1: plain sums (average pooling, divided by the
+// length when the units are joined); MODE 2: element-wise maxima.
+enum : int { POOL_WEIGHTED = 0, POOL_SUM = 1, POOL_MAXIMUM = 2 };
+
 template <bool BF16>
+__device__ __forceinline__ void widen16(const uint4 &q, float (&h)[BF16 ? 8 : 4])
+{
+    if (BF16) {
+        const unsigned v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h[2 * e] = __uint_as_float(v[e] << 16);
+            h[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+        }
+    } else {
+        h[0] = __uint_as_float(q.x);
+        h[1] = __uint_as_float(q.y);
+        h[2] = __uint_as_float(q.z);
+        h[3] = __uint_as_float(q.w);
+    }
+}
+
+template <bool BF16, int MODE>
 __global__ __launch_bounds__(256) void pool_partial_kernel(
     const void *__restrict__ hidden, int d, const float *__restrict__ entropy,
     const int32_t *__restrict__ offsets, int32_t B, float inv_alpha, const float *__restrict__ lse_new,
@@ -161,9 +183,11 @@ __global__ __launch_bounds__(256) void pool_partial_kernel(
     const int b = find_segment(unit_start, B, u);
     const long t0 = (long)offsets[b] + (long)(u - unit_start[b]) * POOL_UNIT;
     const int n = (int)min((long)POOL_UNIT, (long)offsets[b + 1] - t0);
-    if (threadIdx.x < POOL_UNIT)
-        w[threadIdx.x] = threadIdx.x < n ? __expf(entropy[t0 + threadIdx.x] * inv_alpha - lse_new[b]) : 0.f;
-    __syncthreads();
+    if (MODE == POOL_WEIGHTED) {
+        if (threadIdx.x < POOL_UNIT)
+            w[threadIdx.x] = threadIdx.x < n ? __expf(entropy[t0 + threadIdx.x] * inv_alpha - lse_new[b]) : 0.f;
+        __syncthreads();
+    }
 
     constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte load
     const int nchunk = d / VEC;
@@ -172,54 +196,58 @@ __global__ __launch_bounds__(256) void pool_partial_kernel(
         float acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
-            acc[e] = 0.f;
+            acc[e] = MODE == POOL_MAXIMUM ? NEG_INF : 0.f;
         const unsigned char *p = (const unsigned char *)hidden + (t0 * d + (long)c * VEC) * (BF16 ? 2 : 4);
         const long stride = (long)d * (BF16 ? 2 : 4);
-        int i = 0;
-        for (; i + 4 <= n; i += 4) {
-            uint4 q[4];
+        auto fold = [&](const uint4 &q, int i) {
+            float h[VEC];
+            widen16<BF16>(q, h);
+            const float wi = MODE == POOL_WEIGHTED ? w[i] : 1.f;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int e = 0; e < VEC; ++e)
+                acc[e] = MODE == POOL_MAXIMUM ? fmaxf(acc[e], h[e])
+                         : MODE == POOL_SUM   ? acc[e] + h[e]
+                                              : fmaf(wi, h[e], acc[e]);
+        };
+        int i = 0;
+        for (; i + 8 <= n; i += 8) {  // eight rows in flight per thread
+            uint4 q[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
                 q[r] = *(const uint4 *)(p + (long)(i + r) * stride);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float wi = w[i + r];
-                if (BF16) {
-                    const unsigned v[4] = {q[r].x, q[r].y, q[r].z, q[r].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        acc[2 * e] = fmaf(wi, __uint_as_float(v[e] << 16), acc[2 * e]);
-                        acc[2 * e + 1] = fmaf(wi, __uint_as_float(v[e] & 0xffff0000u), acc[2 * e + 1]);
-                    }
-                } else {
-                    acc[0] = fmaf(wi, __uint_as_float(q[r].x), acc[0]);
-                    acc[1] = fmaf(wi, __uint_as_float(q[r].y), acc[1]);
-                    acc[2] = fmaf(wi, __uint_as_float(q[r].z), acc[2]);
-                    acc[3] = fmaf(wi, __uint_as_float(q[r].w), acc[3]);
-                }
-            }
+            for (int r = 0; r < 8; ++r)
+                fold(q[r], i + r);
         }
-        for (; i < n; ++i) {
-            const uint4 q = *(const uint4 *)(p + (long)i * stride);
-            const float wi = w[i];
-            if (BF16) {
-                const unsigned v[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[2 * e] = fmaf(wi, __uint_as_float(v[e] << 16), acc[2 * e]);
-                    acc[2 * e + 1] = fmaf(wi, __uint_as_float(v[e] & 0xffff0000u), acc[2 * e + 1]);
-                }
-            } else {
-                acc[0] = fmaf(wi, __uint_as_float(q.x), acc[0]);
-                acc[1] = fmaf(wi, __uint_as_float(q.y), acc[1]);
-                acc[2] = fmaf(wi, __uint_as_float(q.z), acc[2]);
-                acc[3] = fmaf(wi, __uint_as_float(q.w), acc[3]);
-            }
-        }
+        for (; i < n; ++i)
+            fold(*(const uint4 *)(p + (long)i * stride), i);
 #pragma unroll
         for (int e = 0; e < VEC; e += 4)
             *(float4 *)(out + (long)c * VEC + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
     }
+}
+
+// ---- Table 3 alternatives: join a sequence's unit partials (sum / length, or maximum) -------
+template <int MODE>
+__global__ __launch_bounds__(256) void pool_finalize_plain_kernel(const float *__restrict__ partial,
+                                                                  const int32_t *__restrict__ unit_start,
+                                                                  const int32_t *__restrict__ offsets, int d,
+                                                                  float *__restrict__ out_pooled)
+{
+    const int b = blockIdx.x;
+    const int k = blockIdx.y * 256 + threadIdx.x;
+    if (k >= d)
+        return;
+    const int u0 = unit_start[b], u1 = unit_start[b + 1];
+    const int len = offsets[b + 1] - offsets[b];
+    float r = (MODE == POOL_MAXIMUM && len > 0) ? NEG_INF : 0.f;  // an empty sequence pools to zero
+    for (int u = u0; u < u1; ++u) {
+        const float v = partial[(long)u * d + k];
+        r = MODE == POOL_MAXIMUM ? fmaxf(r, v) : r + v;
+    }
+    if (MODE == POOL_SUM && len > 0)
+        r *= 1.0f / (float)len;
+    out_pooled[(long)b * d + k] = r;
 }
 
 // ---- sum a sequence's partials in unit order, add the rescaled old state ------------------
@@ -300,11 +328,11 @@ __global__ __launch_bounds__(256) void plp_fold1_kernel(const void *__restrict__
     }
 }
 
-// ---- Table 3 alternatives -----------------------------------------------------------------
+// ---- Table 3 alternative: the last token's hidden state ------------------------------------
 template <bool BF16>
-__global__ __launch_bounds__(256) void pool_plain_kernel(const void *__restrict__ hidden, int d,
-                                                         const int32_t *__restrict__ offsets, int kind,
-                                                         float *__restrict__ out_pooled)
+__global__ __launch_bounds__(256) void pool_last_kernel(const void *__restrict__ hidden, int d,
+                                                        const int32_t *__restrict__ offsets,
+                                                        float *__restrict__ out_pooled)
 {
     constexpr int VEC = BF16 ? 8 : 4;
     const int b = blockIdx.x;
@@ -312,40 +340,17 @@ __global__ __launch_bounds__(256) void pool_plain_kernel(const void *__restrict_
     if (c * VEC >= d)
         return;
     const long lo = offsets[b], hi = offsets[b + 1];
-    float acc[VEC];
+    float h[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e)
-        acc[e] = (kind == 1 && hi > lo) ? NEG_INF : 0.f;
-    const long first = kind == 2 ? (hi > lo ? hi - 1 : hi) : lo;
-    for (long t = first; t < hi; ++t) {
-        const uint4 q = *(const uint4 *)((const unsigned char *)hidden + (t * d + (long)c * VEC) * (BF16 ? 2 : 4));
-        float h[VEC];
-        if (BF16) {
-            const unsigned v[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                h[2 * e] = __uint_as_float(v[e] << 16);
-                h[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
-            }
-        } else {
-            h[0] = __uint_as_float(q.x);
-            h[1] = __uint_as_float(q.y);
-            h[2] = __uint_as_float(q.z);
-            h[3] = __uint_as_float(q.w);
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-            acc[e] = kind == 1 ? fmaxf(acc[e], h[e]) : acc[e] + h[e];
-    }
-    if (kind == 0 && hi > lo) {
-        const float inv = 1.0f / (float)(hi - lo);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-            acc[e] *= inv;
+        h[e] = 0.f;  // an empty sequence pools to zero
+    if (hi > lo) {
+        const uint4 q = *(const uint4 *)((const unsigned char *)hidden + ((hi - 1) * d + (long)c * VEC) * (BF16 ? 2 : 4));
+        widen16<BF16>(q, h);
     }
 #pragma unroll
     for (int e = 0; e < VEC; ++e)
-        out_pooled[(long)b * d + (long)c * VEC + e] = acc[e];
+        out_pooled[(long)b * d + (long)c * VEC + e] = h[e];
 }
 
 }  // namespace
@@ -386,10 +391,10 @@ hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
     if (units > 0x7fffffffL)
         return hipErrorInvalidValue;
     if (bf16)
-        hipLaunchKernelGGL(pool_partial_kernel<true>, dim3((unsigned)units), dim3(256), 0, st, a.hidden,
+        hipLaunchKernelGGL((pool_partial_kernel<true, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
                            a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
     else
-        hipLaunchKernelGGL(pool_partial_kernel<false>, dim3((unsigned)units), dim3(256), 0, st, a.hidden,
+        hipLaunchKernelGGL((pool_partial_kernel<false, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
                            a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
     hipLaunchKernelGGL(pool_finalize_kernel, dim3(a.B, (a.d + 255) / 256), dim3(256), 0, st, a.partial,
                        a.unit_start, a.slot, a.d, a.state_pooled, a.state_scale, a.lse_new, a.out_pooled,
@@ -397,17 +402,46 @@ hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B, int kind,
-                      float *out_pooled, hipStream_t st)
+hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B, int64_t T,
+                      int kind, int32_t *unit_start, float *partial, float *out_pooled, hipStream_t st)
 {
     if (B <= 0)
         return hipSuccess;
-    const int vec = dtype == DT_BF16 ? 8 : 4;
-    const dim3 grid(B, (d / vec + 255) / 256);
-    if (dtype == DT_BF16)
-        hipLaunchKernelGGL(pool_plain_kernel<true>, grid, dim3(256), 0, st, hidden, d, offsets, kind, out_pooled);
-    else
-        hipLaunchKernelGGL(pool_plain_kernel<false>, grid, dim3(256), 0, st, hidden, d, offsets, kind, out_pooled);
+    const bool bf16 = dtype == DT_BF16;
+    if (kind == 2) {  // last token: one row per sequence
+        const int vec = bf16 ? 8 : 4;
+        const dim3 grid(B, (d / vec + 255) / 256);
+        if (bf16)
+            hipLaunchKernelGGL(pool_last_kernel<true>, grid, dim3(256), 0, st, hidden, d, offsets, out_pooled);
+        else
+            hipLaunchKernelGGL(pool_last_kernel<false>, grid, dim3(256), 0, st, hidden, d, offsets, out_pooled);
+        return hipGetLastError();
+    }
+    // average and maximum stream every token once: same units of <= POOL_UNIT tokens as Eq. 4
+    const long units = pool_units_bound(T, B);
+    if (units > 0x7fffffffL)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(256), 0, st, offsets, B, unit_start);
+    const dim3 fgrid(B, (d + 255) / 256);
+#define EGTP_POOL_PLAIN(BF, MODE)                                                                          \
+    do {                                                                                                   \
+        hipLaunchKernelGGL((pool_partial_kernel<BF, MODE>), dim3((unsigned)units), dim3(256), 0, st, hidden, \
+                           d, nullptr, offsets, B, 0.f, nullptr, unit_start, partial);                     \
+        hipLaunchKernelGGL(pool_finalize_plain_kernel<MODE>, fgrid, dim3(256), 0, st, partial, unit_start, \
+                           offsets, d, out_pooled);                                                        \
+    } while (0)
+    if (kind == 0) {
+        if (bf16)
+            EGTP_POOL_PLAIN(true, POOL_SUM);
+        else
+            EGTP_POOL_PLAIN(false, POOL_SUM);
+    } else {
+        if (bf16)
+            EGTP_POOL_PLAIN(true, POOL_MAXIMUM);
+        else
+            EGTP_POOL_PLAIN(false, POOL_MAXIMUM);
+    }
+#undef EGTP_POOL_PLAIN
     return hipGetLastError();
 }
 

@@ -74,7 +74,7 @@ hipError_t segment_ids(const int32_t *offsets, int32_t B, int64_t T, int32_t *se
 
 // Eq. 3 / Eq. 4 / Eq. 8 over ragged offsets.  A sequence is cut into units of at most
 // POOL_UNIT tokens; unit_start[B+1] is the exclusive scan of units per sequence.
-constexpr int POOL_UNIT = 64;
+constexpr int POOL_UNIT = 128;
 inline int64_t pool_units_bound(int64_t T, int32_t B) { return (T + POOL_UNIT - 1) / POOL_UNIT + B; }
 
 struct PoolArgs {
@@ -99,9 +99,10 @@ struct PoolArgs {
 };
 hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st);
 
-// Table 3 alternatives: kind 0 average, 1 max, 2 last token.
-hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B,
-                      int kind, float *out_pooled, hipStream_t st);
+// Table 3 alternatives: kind 0 average, 1 max, 2 last token.  Average and max use the unit table
+// (unit_start[B+1]) and the unit partials ([pool_units_bound(T, B) x d]) of the weighted pooling.
+hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offsets, int32_t B, int64_t T,
+                      int kind, int32_t *unit_start, float *partial, float *out_pooled, hipStream_t st);
 
 // Prediction head.
 struct HeadArgs {

@@ -276,6 +276,23 @@ def test_ablation_poolers(gpu):
     assert np.abs(pooled.cpu().numpy() - want).max() < 1e-5
 
 
+def test_pooling_unit_boundaries(gpu):
+    """Sequences just below, at and above one and two pooling units (128 tokens per workgroup), an empty
+    one and a long one: weighted pooling (Eq. 3-4) and the three ablation poolers against the oracle."""
+    lens = (127, 128, 129, 0, 255, 256, 257, 1, 700)
+    w = _small_bf16(seed=41, B=len(lens), d=136, V=300, d_h=16, lengths=lens)
+    got = _run(gpu, w)
+    ooff = oracle.offsets_from_lengths(lens)
+    head = oracle.Head(w.w1, w.w2)
+    assert_egtp_close(got, oracle.egtp(w.hidden, ooff, w.w_lm, head))
+    sc = _scorer(gpu, w)
+    off = _offsets_on_gpu(gpu, sc, lens)
+    for kind in (gpu.EGTP_POOL_AVERAGE, gpu.EGTP_POOL_MAX, gpu.EGTP_POOL_LAST):
+        pooled, _ = sc.pool_ablation(gpu.to_device(w.hidden), off, kind, want_pred=False)
+        want = oracle.pool_ablation(w.hidden, ooff, kind)
+        assert np.abs(pooled.cpu().numpy() - want).max() <= 1e-5 * max(1.0, np.abs(want).max()), kind
+
+
 # ----------------------------------------------------------------------------- PLP (Eq. 8)
 def _plp_setup(gpu, seed=31, B=5, d=256, V=900, d_h=24, steps=4):
     w = _small_bf16(seed=seed, B=B, d=d, V=V, d_h=d_h, lo=1, hi=60)
