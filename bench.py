@@ -64,13 +64,38 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
     for i in range(max(args.warmup, 1)):
         gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
     torch.cuda.synchronize()
-    gpu.egtp_profile_enable(sc.ctx, True, min(1024, steps))
-    t0 = time.perf_counter()
-    for i in range(steps):
-        gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    k1_ms = gpu.egtp_profile_read(sc.ctx)
+    if args.graph:
+        # the decode loop as a HIP graph: the 16 distinct steps are captured once and replayed; the fused
+        # kernel is timed with events on 32 eager steps first (no events inside the capture)
+        gpu.egtp_profile_enable(sc.ctx, True, 32)
+        for i in range(32):
+            gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
+        torch.cuda.synchronize()
+        k1_ms = gpu.egtp_profile_read(sc.ctx)
+        gpu.egtp_profile_enable(sc.ctx, False)
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(16):
+                    gpu.plp_step(sc.ctx, hs[i], None, None, None, B, B, pooled, lse, ws, None, pred)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, steps // 16)
+        steps = reps * 16
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        gpu.egtp_profile_enable(sc.ctx, True, min(1024, steps))
+        t0 = time.perf_counter()
+        for i in range(steps):
+            gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        k1_ms = gpu.egtp_profile_read(sc.ctx)
     k1_s = float(k1_ms.mean()) * 1e-3
     flops = 2.0 * spec.d * spec.V * B
     achieved = flops / k1_s / 1e12
@@ -80,7 +105,8 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"plp_decode: {B} live sequences x 1 new token per step, d={spec.d}, V={spec.V}, "
-                               f"remaining-length head {spec.d}->{spec.d_h}->1, seed {spec.seed}", "B": B},
+                               f"remaining-length head {spec.d}->{spec.d_h}->1, seed {spec.seed}", "B": B,
+                   "launch": "hip graph of 16 steps" if args.graph else "eager"},
         "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": None, "avg_launch_ms": k1_s * 1e3, "launches": int(k1_ms.size),
@@ -133,6 +159,8 @@ def main() -> int:
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--graph", action="store_true",
+                    help="--workload plp_decode: replay the decode steps from a captured HIP graph")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--copy-calibration", action="store_true",

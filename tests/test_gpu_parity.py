@@ -450,3 +450,45 @@ def test_head_keeps_the_pooled_vector_in_fp32(gpu):
     assert err.max() < bar, err.max()
     hi = (got["pooled"].view(np.uint32) & np.uint32(0xffff0000)).view(np.float32).astype(np.float64)
     assert (np.abs(oracle.predict(hi, head) - want) / scale).max() > 2 * bar
+
+
+def test_plp_steps_replayed_from_a_graph(gpu):
+    """The scoring calls only enqueue kernels on the caller's stream, so a decode loop can be captured in a
+    HIP graph.  Three steps are captured once and replayed four times, with eager work and
+    synchronisations in between; every replay must leave exactly what the same twelve eager steps leave."""
+    import torch
+    w, sc, gen, _ = _plp_setup(gpu, seed=43, steps=3)
+    B, d = w.spec.B, w.spec.d
+    hs = [gpu.to_device(g) for g in gen]
+
+    def fresh():
+        return (torch.zeros(B, d, dtype=torch.float32, device="cuda"),
+                torch.full((B,), -math.inf, dtype=torch.float32, device="cuda"),
+                [torch.empty(B, dtype=torch.float32, device="cuda") for _ in hs])
+
+    ws = sc.workspace(B, B)
+    pooled_e, lse_e, pred_e = fresh()
+    pooled_g, lse_g, pred_g = fresh()
+    # the first call on a device raises kernel attributes: keep that outside the capture
+    warm_p, warm_l, warm_r = fresh()
+    gpu.plp_step(sc.ctx, hs[0], None, None, None, B, B, warm_p, warm_l, ws, None, warm_r[0])
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for h, r in zip(hs, pred_g):
+                gpu.plp_step(sc.ctx, h, None, None, None, B, B, pooled_g, lse_g, ws, None, r)
+    torch.cuda.synchronize()
+    ws_e = sc.workspace(B, B).clone()
+    for replay in range(4):
+        graph.replay()
+        for h, r in zip(hs, pred_e):
+            gpu.plp_step(sc.ctx, h, None, None, None, B, B, pooled_e, lse_e, ws_e, None, r)
+        scratch = torch.randn(1 << 16, device="cuda").sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(pooled_g, pooled_e) and torch.equal(lse_g, lse_e), replay
+        for a, b in zip(pred_g, pred_e):
+            assert torch.equal(a, b), replay
+        assert bool(torch.isfinite(scratch))
