@@ -115,6 +115,57 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
     return 0
 
 
+def bench_rl(args, gpu, wl, np, torch) -> int:
+    """One-to-many sampling workload (64 prompts x 16 samples, d = 5120, V = 151936): EGTP on the prompts, the
+    state copied to each sample's slot, then one step = a ragged plp_step folding the 64 tokens every still-live
+    sample has generated since the last call (decode step 64; samples addressed through `slot`)."""
+    spec = wl.SPECS["rl_prompts"]
+    w = wl.make(spec)
+    td = gpu.to_device
+    S_PER = 16
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    off = sc.build_offsets(torch.from_numpy(w.lengths).cuda(), w.T)
+    out = sc.score(td(w.hidden), off)
+    pooled = out["pooled"].repeat_interleave(S_PER, dim=0).contiguous()
+    lse = out["lse"].repeat_interleave(S_PER, dim=0).contiguous()
+    cont = wl.rl_continuations(spec, S_PER)
+    live = np.nonzero(cont >= 64)[0].astype(np.int32)
+    T = int(live.size) * 64
+    hid = td(wl.draw_hidden(spec, np.random.default_rng([spec.seed, 7, 64]), T))
+    coff = torch.from_numpy(np.arange(live.size + 1, dtype=np.int32) * 64).cuda()
+    slot = torch.from_numpy(live).cuda()
+    pred = torch.empty(live.size, dtype=torch.float32, device="cuda")
+    ws = sc.workspace(T, int(live.size))
+
+    def step():
+        gpu.plp_step(sc.ctx, hid, coff, None, slot, int(live.size), T, pooled, lse, ws, None, pred)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    gpu.egtp_profile_enable(sc.ctx, True, max(1, min(1024, args.steps)))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k1_s = float(gpu.egtp_profile_read(sc.ctx).mean()) * 1e-3
+    achieved = 2.0 * spec.d * spec.V * T / k1_s / 1e12
+    print(json.dumps({
+        "metric": f"tokens folded/sec (ragged PLP step, d={spec.d} V={spec.V}, 64 tokens per live sample)",
+        "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": max(args.warmup, 1), "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"rl: {spec.B} prompts x {S_PER} samples, {live.size} live at decode step 64, {T} new "
+                               f"tokens per call, d={spec.d}, V={spec.V}, head {spec.d}->{spec.d_h}->1, seed {spec.seed}",
+                   "B": int(live.size), "T": T},
+        "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
+                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_ms": k1_s * 1e3},
+        "cpu_baseline": None}), flush=True)
+    return 0
+
+
 def bench_train(args, gpu, wl, np, torch) -> int:
     """Head training workload: one step = egtp_head_train_step on a batch of 16 pooled vectors
     (d = 4096, d_h = 1024, K = 20; batch size, K and optimiser of the paper's experimental setup).
@@ -155,7 +206,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "train"],
+    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "rl", "train"],
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
@@ -182,6 +233,8 @@ def main() -> int:
         return bench_plp(args, gpu, wl, np, torch)
     if args.workload == "train":
         return bench_train(args, gpu, wl, np, torch)
+    if args.workload == "rl":
+        return bench_rl(args, gpu, wl, np, torch)
     spec = wl.SPECS[args.workload]
     t0 = time.time()
     w = wl.make(spec)
