@@ -254,6 +254,24 @@ def test_vocabulary_permutation_invariance(gpu):
     assert np.abs(a["entropy"] - b["entropy"]).max() < 2e-5
 
 
+def test_token_order_invariance_inside_a_sequence(gpu):
+    """Eq. 2-4 do not look at positions: permuting the tokens of each sequence permutes the entropies and
+    leaves pooled vector, lse and prediction unchanged (up to the order of the fp32 sums)."""
+    lens = (300, 1, 77, 130)
+    w = _small_bf16(seed=47, B=4, d=128, V=700, d_h=16, lengths=lens)
+    a = _run(gpu, w)
+    off = oracle.offsets_from_lengths(lens)
+    rng = np.random.default_rng(1)
+    perm = np.concatenate([off[b] + rng.permutation(lens[b]) for b in range(len(lens))])
+    w.hidden = np.ascontiguousarray(w.hidden[perm])
+    b = _run(gpu, w)
+    assert np.array_equal(a["entropy"][perm], b["entropy"])          # a token's entropy depends on nothing else
+    for s in range(len(lens)):
+        assert rel_l2(b["pooled"][s], a["pooled"][s]) < 1e-5
+    assert np.abs(a["lse"] - b["lse"]).max() < 1e-5
+    assert_pred_close(b["pred"], a["pred"].astype(np.float64))
+
+
 def test_ablation_poolers(gpu):
     lens = (4, 0, 33, 1)
     w = _small_bf16(seed=29, B=4, d=128, V=300, d_h=16, lengths=lens)
