@@ -212,6 +212,8 @@ def main() -> int:
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
     ap.add_argument("--graph", action="store_true",
                     help="--workload plp_decode: replay the decode steps from a captured HIP graph")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the library GEMM of the same shape with the logits written out (context only)")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -243,7 +245,8 @@ def main() -> int:
           file=sys.stderr, flush=True)
 
     td = gpu.to_device
-    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    w_lm_dev = td(w.w_lm)
+    sc = gpu.Scorer(w_lm_dev, gpu.make_head(td(w.w1), td(w.w2)))
     hidden = td(w.hidden)
     lengths = torch.from_numpy(w.lengths).cuda()
     offsets = torch.empty(B + 1, dtype=torch.int32, device="cuda")
@@ -294,6 +297,25 @@ def main() -> int:
                  "random_operands_tflops": float(rnd[2:].mean()), "zero_operands_tflops": float(zero[2:].mean()),
                  "achieved_over_random": achieved / float(rnd[2:].mean())}
 
+    # Context, not part of the path: what the vendor GEMM needs for hidden . W_lm^T of the same shape on the same
+    # box when the [T x V] logits are written to HBM in bf16 (the tensor this path never writes).
+    lib_gemm = None
+    if args.library_gemm:
+        w_dev = w_lm_dev
+        logits = torch.empty(T, spec.V, dtype=torch.bfloat16, device="cuda")
+        for _ in range(2):
+            torch.mm(hidden, w_dev.t(), out=logits)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            torch.mm(hidden, w_dev.t(), out=logits)
+        e1.record()
+        torch.cuda.synchronize()
+        gms = e0.elapsed_time(e1) / 5
+        lib_gemm = {"what": "torch.mm(hidden, W_lm^T) -> bf16 logits in HBM, same box", "ms": gms,
+                    "tflops": flops_per_launch / (gms * 1e-3) / 1e12, "logits_bytes": int(logits.numel()) * 2}
+        del logits
+
     cpu = None
     if args.oracle_tokens > 0:
         import oracle
@@ -323,6 +345,7 @@ def main() -> int:
                      "traffic": traffic if args.workload == "serving" else None,
                      "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
         "mfma_probe": probe,
+        "library_gemm": lib_gemm,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
