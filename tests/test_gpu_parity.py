@@ -510,3 +510,71 @@ def test_plp_steps_replayed_from_a_graph(gpu):
         for a, b in zip(pred_g, pred_e):
             assert torch.equal(a, b), replay
         assert bool(torch.isfinite(scratch))
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_seeded_random_shapes_against_the_oracle(gpu, case):
+    """Twelve seeded draws of batch size, ragged lengths (empty sequences included), hidden size,
+    vocabulary, head width, biases, temperature and scalar or K-bin output, each against the oracle."""
+    rng = np.random.default_rng(1000 + case)
+    B = int(rng.integers(1, 10))
+    lens = tuple(int(x) for x in np.where(rng.random(B) < 0.15, 0, rng.integers(1, 420, size=B)))
+    d = 8 * int(rng.integers(1, 66))
+    V = int(rng.integers(1, 3000))
+    d_h = int(rng.integers(1, 70))
+    alpha = float(rng.choice([0.5, 1.0, 1.0, 2.5]))
+    w = _small_bf16(seed=2000 + case, B=B, d=d, V=V, d_h=d_h, lengths=lens)
+    b1 = (0.1 * rng.normal(size=d_h)).astype(np.float32) if rng.random() < 0.5 else None
+    if rng.random() < 0.5:
+        K = int(rng.integers(2, 40))
+        w2 = wl.to_bf16_bits(rng.normal(0, 1.0, size=(K, d_h)).astype(np.float32))
+        b2 = rng.normal(size=K).astype(np.float32)
+        centers = np.sort(rng.uniform(1.0, 4096.0, size=K)).astype(np.float32)
+    else:
+        w2, centers = w.w2, None
+        b2 = rng.normal(size=1).astype(np.float32) if rng.random() < 0.5 else None
+    got = _run(gpu, w, alpha=alpha, b1=b1, b2=b2, w2=w2, centers=centers)
+    head = oracle.Head(w.w1, w2, b1, b2, None if centers is None else centers.astype(np.float64))
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(lens), w.w_lm, head, alpha)
+    assert_egtp_close(got, want)
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_seeded_random_plp_histories_against_the_oracle(gpu, case):
+    """Seeded decode histories: a random subset of the state slots is live at each call and receives a
+    random number (0..70) of new tokens through `slot`; after every call each live slot must hold what
+    the oracle computes from that slot's whole history (Eq. 8 as EGTP on the concatenation)."""
+    import torch
+    rng = np.random.default_rng(3000 + case)
+    S = int(rng.integers(2, 8))                       # state slots
+    d = 8 * int(rng.integers(2, 40))
+    V = int(rng.integers(50, 2000))
+    d_h = int(rng.integers(2, 40))
+    w = _small_bf16(seed=4000 + case, B=S, d=d, V=V, d_h=d_h, lengths=tuple(int(x) for x in rng.integers(0, 90, size=S)))
+    sc = _scorer(gpu, w)
+    head = oracle.Head(w.w1, w.w2)
+    poff = oracle.offsets_from_lengths(w.lengths)
+    history = [w.hidden[poff[b]:poff[b + 1]] for b in range(S)]
+    out = sc.score(gpu.to_device(w.hidden), _offsets_on_gpu(gpu, sc, w.lengths))
+    pooled, lse = out["pooled"].clone(), out["lse"].clone()
+    for call in range(4):
+        live = np.sort(rng.choice(S, size=int(rng.integers(1, S + 1)), replace=False)).astype(np.int32)
+        n_new = rng.integers(0, 71, size=live.size).astype(np.int32)
+        if n_new.sum() == 0:
+            n_new[0] = 1
+        T_new = int(n_new.sum())
+        chunk = wl.draw_hidden(w.spec, np.random.default_rng([3000 + case, call]), T_new)
+        chunk = wl.to_bf16_bits(chunk) if chunk.dtype != np.uint16 else chunk
+        coff = oracle.offsets_from_lengths(n_new)
+        pred = sc.step(gpu.to_device(chunk), pooled, lse, offsets_new_dev=torch.from_numpy(coff).cuda(),
+                       offsets_new_host=coff, slot_dev=torch.from_numpy(live).cuda())
+        for i, sl in enumerate(live):
+            history[sl] = np.concatenate([history[sl], chunk[coff[i]:coff[i + 1]]])
+        lens = [history[sl].shape[0] for sl in live]
+        want = oracle.egtp(np.concatenate([history[sl] for sl in live]), oracle.offsets_from_lengths(lens), w.w_lm, head)
+        pooled_np, lse_np = pooled.cpu().numpy(), lse.cpu().numpy()
+        for i, sl in enumerate(live):
+            if lens[i] > 0:
+                assert rel_l2(pooled_np[sl], want.pooled[i]) <= TOL_POOLED_REL_L2, (call, sl)
+                assert abs(lse_np[sl] - want.lse[i]) <= TOL_LSE_ABS, (call, sl)
+        assert_pred_close(pred.cpu().numpy(), want.pred)
