@@ -166,6 +166,45 @@ def bench_rl(args, gpu, wl, np, torch) -> int:
     return 0
 
 
+def bench_pool(args, gpu, wl, np, torch) -> int:
+    """Ablation poolers (Table 3) on the serving batch: one step = average pooling of all 137720 hidden states
+    over the ragged offsets (no LM head, no entropy).  The roofline is HBM: every hidden state is read once."""
+    spec = wl.SPECS["serving"]
+    w = wl.make(spec)
+    td = gpu.to_device
+    sc = gpu.Scorer(td(w.w_lm[:256]), gpu.make_head(td(w.w1), td(w.w2)))   # the poolers never touch W_lm
+    hidden = td(w.hidden)
+    T, B = hidden.shape[0], spec.B
+    off = sc.build_offsets(torch.from_numpy(w.lengths).cuda(), T)
+    ws = sc.workspace(T, B)
+    pooled = torch.empty(B, spec.d, dtype=torch.float32, device="cuda")
+    steps = args.steps if args.steps != 10 else 100
+    times = {}
+    for kind, name in ((gpu.EGTP_POOL_AVERAGE, "average"), (gpu.EGTP_POOL_MAX, "max"), (gpu.EGTP_POOL_LAST, "last")):
+        for _ in range(max(args.warmup, 1)):
+            gpu.egtp_pool_ablation(sc.ctx, hidden, off, None, B, T, kind, ws, pooled, None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            gpu.egtp_pool_ablation(sc.ctx, hidden, off, None, B, T, kind, ws, pooled, None)
+        torch.cuda.synchronize()
+        times[name] = (time.perf_counter() - t0) / steps
+    dt = times["average"]
+    gbps = 2.0 * spec.d * T / dt / 1e9
+    print(json.dumps({
+        "metric": f"tokens pooled/sec (average pooling over ragged offsets, d={spec.d})",
+        "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"pool: the serving batch ({B} ragged sequences, {T} tokens, d={spec.d}), poolers only",
+                   "B": B, "T": T},
+        "ms_per_step_by_pooler": {k: v * 1e3 for k, v in times.items()},
+        "roofline": {"kernel": "pool_partial_kernel (sum mode) + join", "bound": "hbm", "achieved": gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None},
+        "cpu_baseline": None}), flush=True)
+    return 0
+
+
 def bench_train(args, gpu, wl, np, torch) -> int:
     """Head training workload: one step = egtp_head_train_step on a batch of 16 pooled vectors
     (d = 4096, d_h = 1024, K = 20; batch size, K and optimiser of the paper's experimental setup).
@@ -206,7 +245,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "rl", "train"],
+    ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "rl", "pool", "train"],
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
@@ -237,6 +276,8 @@ def main() -> int:
         return bench_train(args, gpu, wl, np, torch)
     if args.workload == "rl":
         return bench_rl(args, gpu, wl, np, torch)
+    if args.workload == "pool":
+        return bench_pool(args, gpu, wl, np, torch)
     spec = wl.SPECS[args.workload]
     t0 = time.time()
     w = wl.make(spec)
