@@ -80,7 +80,8 @@ typedef struct {
     int32_t d;          /* hidden size */
     int32_t vocab;      /* vocabulary size V */
     egtp_dtype dtype;   /* storage type of hidden states and w_lm */
-    const void *w_lm;   /* [vocab x d] device, must outlive the context */
+    const void *w_lm;   /* [vocab x d] device, must outlive the context.  bf16 contexts may pass NULL
+                         * and live on a packed copy alone (egtp_adopt_packed_w_lm) */
     float alpha;        /* pooling temperature, finite and > 0; 1.0f is Eq. 3 as printed */
     egtp_head head_len; /* EGTP: predicted total length */
     egtp_head head_rem; /* PLP: predicted remaining length; w1 == NULL means "use head_len" */
@@ -99,9 +100,16 @@ egtp_status egtp_destroy(egtp_ctx *ctx);
  * its workspace first -- fine for large prefill batches, wasteful for decode steps.  Calling it
  * again re-packs (after w_lm changed); packed_dev == NULL forgets the copy.  Changing between
  * "packed" and "not packed" changes egtp_workspace_bytes().  fp32 contexts: bytes = 0,
- * packing is EGTP_ERR_DTYPE. */
+ * packing is EGTP_ERR_DTYPE.  A context created with w_lm == NULL has nothing to pack from
+ * (EGTP_ERR_NULL). */
 size_t egtp_packed_w_lm_bytes(const egtp_ctx *ctx);
 egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *stream);
+/* Registers a packed copy that already exists -- built earlier by egtp_pack_w_lm of a context with
+ * the same d, vocab and dtype -- without touching it.  With it a context needs no row-major W_lm at
+ * all: the Eq. 2 kernel only ever reads the packed copy, so a caller that keeps W_lm elsewhere (or
+ * nowhere) saves 2 d vocab bytes.  Same alignment, size and lifetime rules as above; scoring
+ * calls of a context that has neither w_lm nor a packed copy return EGTP_ERR_NULL. */
+egtp_status egtp_adopt_packed_w_lm(egtp_ctx *ctx, const void *packed_dev, size_t bytes);
 
 /* Bytes of workspace sufficient for any egtp_score / plp_step / egtp_pool_ablation call with
  * at most max_tokens tokens and max_seqs sequences.  0 if an argument is invalid. */
@@ -132,6 +140,15 @@ egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets
                        size_t workspace_bytes, float *entropy_out, float *pooled_out,
                        float *lse_out, float *pred_out, void *stream);
 
+/* egtp_score for a K-bin head (head_len.n_out = K > 1) that also hands out the distribution the
+ * predicted length is the expectation of (Eq. 6): p_hat_out [B x K] fp32, row b = softmax over the
+ * K head outputs of sequence b (each row sums to 1; pred_out[b] = sum_j p_hat[b][j] c_j).
+ * A scalar head (n_out == 1) is EGTP_ERR_SHAPE; everything else as egtp_score. */
+egtp_status egtp_score_dist(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                            const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
+                            size_t workspace_bytes, float *entropy_out, float *pooled_out,
+                            float *lse_out, float *pred_out, float *p_hat_out, void *stream);
+
 /* One PLP update (Eq. 8) for B live sequences: fold new tokens into each sequence's running
  * state and predict the remaining length with head_rem.
  *   hidden_new       [T_new x d] hidden states of the newly generated tokens
@@ -150,6 +167,14 @@ egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offse
                      const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B,
                      int64_t T_new, float *pooled_state, float *lse_state, void *workspace,
                      size_t workspace_bytes, float *entropy_out, float *rem_pred_out, void *stream);
+
+/* plp_step for a K-bin remaining-length head, also writing its distribution (Eq. 6):
+ * p_hat_out [B x K] fp32 as in egtp_score_dist (row b belongs to sequence b, whatever its slot). */
+egtp_status plp_step_dist(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                          const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B,
+                          int64_t T_new, float *pooled_state, float *lse_state, void *workspace,
+                          size_t workspace_bytes, float *entropy_out, float *rem_pred_out,
+                          float *p_hat_out, void *stream);
 
 /* Average / max / last-token pooling over the same ragged layout (Table 3's alternatives),
  * followed by head_len.  pooled_out [B x d] fp32, pred_out [B] fp32 (optional).  An empty
@@ -204,6 +229,21 @@ size_t egtp_head_train_workspace_bytes(int32_t B, int32_t d, int32_t d_h, int32_
 egtp_status egtp_head_train_step(const egtp_head_train *head, const float *x, const int32_t *bin,
                                  const float *y, const int32_t *steps_per_seq, int32_t n_seqs, int32_t B,
                                  void *workspace, size_t workspace_bytes, float *loss_out, void *stream);
+
+/* Diagnostic: how the fused LM-head + entropy kernel (Eq. 2) would be launched for T tokens --
+ * one workgroup per (block of tokens_per_block tokens, range of tiles_per_range vocabulary tiles of
+ * rows_per_tile rows); each leaves one partial (max, sum, weighted sum) triple per token, merged
+ * afterwards.  paced = 1 when the bf16 kernel's workgroups keep each other in step (ranges longer
+ * than four tiles).  Pure host arithmetic: no device, no context.  Tests use it to make sure
+ * that a shape reaches the launch configuration they mean to cover. */
+typedef struct {
+    int32_t tokens_per_block, rows_per_tile;
+    int32_t token_blocks, vocab_tiles;
+    int32_t vocab_ranges, tiles_per_range;
+    int32_t paced;
+} egtp_launch_plan;
+egtp_status egtp_launch_plan_query(egtp_dtype dtype, int32_t d, int32_t vocab, int64_t T,
+                                   egtp_launch_plan *out);
 
 /* Measurement aid: when enabled, every egtp_score / plp_step call brackets its fused LM-head +
  * entropy kernel (the Eq. 2 contraction, where nearly all of the work is) with a pair of HIP

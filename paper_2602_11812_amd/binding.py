@@ -25,7 +25,7 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
            "egtp_profile_enable", "egtp_profile_read", "egtp_mfma_probe_sink_floats", "egtp_mfma_probe",
-           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm",
+           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm", "egtp_adopt_packed_w_lm", "egtp_score_dist", "plp_step_dist", "egtp_launch_plan_query",
            "egtp_head_train_workspace_bytes", "egtp_head_train_step", "egtp_sjf_order", "egtp_simulate_batches")
 
 
@@ -55,6 +55,12 @@ class egtp_sched_report(Structure):
     _fields_ = [("n_batches", c_int32), ("actual_tokens", c_int64), ("allocated_tokens", c_int64),
                 ("makespan_steps", c_int64), ("sum_jct_steps", c_int64), ("padding_ratio", c_double),
                 ("avg_jct_steps", c_double), ("throughput", c_double)]
+
+
+class egtp_launch_plan(Structure):
+    _fields_ = [("tokens_per_block", c_int32), ("rows_per_tile", c_int32), ("token_blocks", c_int32),
+                ("vocab_tiles", c_int32), ("vocab_ranges", c_int32), ("tiles_per_range", c_int32),
+                ("paced", c_int32)]
 
 
 class EgtpError(RuntimeError):
@@ -92,6 +98,14 @@ def load_library() -> ctypes.CDLL:
     lib.egtp_score.restype = c_int
     lib.plp_step.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp, vp, c_size_t, vp, vp, vp]
     lib.plp_step.restype = c_int
+    lib.egtp_score_dist.argtypes = [vp, vp, vp, vp, i32, i64, vp, c_size_t, vp, vp, vp, vp, vp, vp]
+    lib.egtp_score_dist.restype = c_int
+    lib.plp_step_dist.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp, vp, c_size_t, vp, vp, vp, vp]
+    lib.plp_step_dist.restype = c_int
+    lib.egtp_adopt_packed_w_lm.argtypes = [vp, vp, c_size_t]
+    lib.egtp_adopt_packed_w_lm.restype = c_int
+    lib.egtp_launch_plan_query.argtypes = [c_int, i32, i32, i64, POINTER(egtp_launch_plan)]
+    lib.egtp_launch_plan_query.restype = c_int
     lib.egtp_pool_ablation.argtypes = [vp, vp, vp, vp, i32, i64, c_int, vp, c_size_t, vp, vp, vp]
     lib.egtp_pool_ablation.restype = c_int
     lib.egtp_packed_w_lm_bytes.argtypes = [vp]
@@ -200,6 +214,20 @@ def egtp_pack_w_lm(ctx, packed_dev, stream=None) -> None:
         raise EgtpError(st, "egtp_pack_w_lm")
 
 
+def egtp_adopt_packed_w_lm(ctx, packed_dev) -> None:
+    st = load_library().egtp_adopt_packed_w_lm(ctx, _dev(packed_dev), packed_dev.numel() * packed_dev.element_size())
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_adopt_packed_w_lm")
+
+
+def egtp_launch_plan_query(dtype: int, d: int, vocab: int, T: int) -> egtp_launch_plan:
+    plan = egtp_launch_plan()
+    st = load_library().egtp_launch_plan_query(int(dtype), int(d), int(vocab), int(T), byref(plan))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_launch_plan_query")
+    return plan
+
+
 def egtp_last_hip_error(ctx) -> int:
     return int(load_library().egtp_last_hip_error(ctx))
 
@@ -220,6 +248,31 @@ def egtp_score(ctx, hidden, offsets_dev, offsets_host, B, T, workspace, entropy_
                                    _stream(stream))
     if st != EGTP_OK:
         raise EgtpError(st, "egtp_score")
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+def egtp_score_dist(ctx, hidden, offsets_dev, offsets_host, B, T, workspace, entropy_out, pooled_out, lse_out,
+                    pred_out, p_hat_out, stream=None) -> None:
+    oh = _host_i32(offsets_host)
+    st = load_library().egtp_score_dist(ctx, _dev(hidden), _dev(offsets_dev), _host_ptr(oh), int(B), int(T),
+                                        _dev(workspace), _nbytes(workspace), _dev(entropy_out), _dev(pooled_out),
+                                        _dev(lse_out), _dev(pred_out), _dev(p_hat_out), _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_score_dist")
+
+
+def plp_step_dist(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state, lse_state,
+                  workspace, entropy_out, rem_pred_out, p_hat_out, stream=None) -> None:
+    oh = _host_i32(offsets_new_host)
+    st = load_library().plp_step_dist(ctx, _dev(hidden_new), _dev(offsets_new_dev), _host_ptr(oh), _dev(slot_dev),
+                                      int(B), int(T_new), _dev(pooled_state), _dev(lse_state), _dev(workspace),
+                                      _nbytes(workspace), _dev(entropy_out), _dev(rem_pred_out), _dev(p_hat_out),
+                                      _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "plp_step_dist")
 
 
 def plp_step(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state, lse_state,

@@ -61,7 +61,10 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     const egtp_config &c = ctx->cfg;
     Carver cv(base);
     Workspace w;
-    const int dh = c.head_len.d_h > c.head_rem.d_h ? c.head_len.d_h : c.head_rem.d_h;
+    // layer 1 leaves more planes when a head has fewer row tiles, so a narrower head can need more
+    // floats than a wider one: the larger of the two bounds, not the bound of the larger width
+    const size_t act_len = head_act_floats_bound(c.d, c.head_len.d_h, B);
+    const size_t act_rem = head_act_floats_bound(c.d, c.head_rem.d_h, B);
     w.entropy = cv.take<float>((size_t)T);
     w.k1_part = cv.take<float>(k1_partial_floats_bound(c.dtype, T, c.d, c.vocab));
     w.k1_pace = cv.take<int>(k1_pace_ints_bound(c.dtype, T, c.d, c.vocab));
@@ -69,7 +72,7 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     w.lse_new = cv.take<float>((size_t)B);
     w.state_scale = cv.take<float>((size_t)B);
     w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
-    w.act = cv.take<float>(head_act_floats_bound(c.d, dh, B));
+    w.act = cv.take<float>(act_len > act_rem ? act_len : act_rem);
     w.hidden_packed = nullptr;
     w.w_packed = nullptr;
     if (c.dtype == EGTP_BF16) {
@@ -150,9 +153,10 @@ egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Work
 }
 
 egtp_status run_head(egtp_ctx *ctx, const egtp_head &h, const float *x, const int32_t *slot, int32_t B,
-                     const Workspace &w, float *pred, hipStream_t st)
+                     const Workspace &w, float *pred, float *p_hat, hipStream_t st)
 {
     HeadArgs a;
+    a.p_hat = p_hat;
     a.x = x;
     a.slot = slot;
     a.B = B;
@@ -219,8 +223,8 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
         return EGTP_ERR_SHAPE;
     if (cfg->d % (cfg->dtype == EGTP_BF16 ? 8 : 4) != 0)
         return EGTP_ERR_SHAPE;  // rows must start on 16-byte boundaries
-    if (!cfg->w_lm)
-        return EGTP_ERR_NULL;
+    if (!cfg->w_lm && cfg->dtype != EGTP_BF16)
+        return EGTP_ERR_NULL;  // a bf16 context can live on a packed copy alone (egtp_adopt_packed_w_lm)
     if (!(cfg->alpha > 0.0f) || !isfinite(cfg->alpha))
         return EGTP_ERR_ALPHA;
     egtp_status s = check_head(cfg->head_len);
@@ -353,6 +357,25 @@ egtp_status egtp_mfma_probe(egtp_ctx *ctx, float *sink, size_t sink_floats, int3
     return e == hipSuccess ? EGTP_OK : hip_fail(ctx, e);
 }
 
+egtp_status egtp_launch_plan_query(egtp_dtype dtype, int32_t d, int32_t vocab, int64_t T, egtp_launch_plan *out)
+{
+    if (!out)
+        return EGTP_ERR_NULL;
+    if (dtype != EGTP_F32 && dtype != EGTP_BF16)
+        return EGTP_ERR_DTYPE;
+    if (d <= 0 || vocab <= 0 || T < 0 || T > 0x7fffffffLL)
+        return EGTP_ERR_SHAPE;
+    const K1Plan p = k1_plan(dtype, T, d, vocab);
+    out->tokens_per_block = p.tb_tokens;
+    out->rows_per_tile = p.tile_v;
+    out->token_blocks = p.ntb;
+    out->vocab_tiles = p.ntiles_v;
+    out->vocab_ranges = p.nsplit;
+    out->tiles_per_range = p.tiles_per_split;
+    out->paced = T > 0 && k1_plan_paces(dtype, p) ? 1 : 0;
+    return EGTP_OK;
+}
+
 size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs)
 {
     if (!ctx || max_tokens < 0 || max_seqs < 0 || max_tokens > 0x7fffffffLL)
@@ -379,9 +402,23 @@ egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *
     }
     if (ctx->cfg.dtype != EGTP_BF16)
         return EGTP_ERR_DTYPE;
+    if (!ctx->cfg.w_lm)
+        return EGTP_ERR_NULL;  // nothing to pack from
     if (((uintptr_t)packed_dev % ALIGN) != 0 || bytes < egtp_packed_w_lm_bytes(ctx))
         return EGTP_ERR_WORKSPACE;
     EGTP_HIP(k1_pack_rows_bf16(ctx->cfg.w_lm, ctx->cfg.vocab, ctx->cfg.d, packed_dev, (hipStream_t)stream));
+    ctx->w_packed = packed_dev;
+    return EGTP_OK;
+}
+
+egtp_status egtp_adopt_packed_w_lm(egtp_ctx *ctx, const void *packed_dev, size_t bytes)
+{
+    if (!ctx || !packed_dev)
+        return EGTP_ERR_NULL;
+    if (ctx->cfg.dtype != EGTP_BF16)
+        return EGTP_ERR_DTYPE;
+    if (((uintptr_t)packed_dev % ALIGN) != 0 || bytes < egtp_packed_w_lm_bytes(ctx))
+        return EGTP_ERR_WORKSPACE;
     ctx->w_packed = packed_dev;
     return EGTP_OK;
 }
@@ -400,17 +437,28 @@ egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_
     return EGTP_OK;
 }
 
-egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+}  // extern "C"
+
+namespace {
+
+// a bf16 context without the row-major W_lm can only score from a packed copy
+bool lm_head_missing(const egtp_ctx *ctx) { return !ctx->cfg.w_lm && !ctx->w_packed; }
+
+egtp_status score_impl(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
                        const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
                        size_t workspace_bytes, float *entropy_out, float *pooled_out, float *lse_out,
-                       float *pred_out, void *stream)
+                       float *pred_out, float *p_hat_out, bool want_p_hat, void *stream)
 {
     egtp_status s = check_common(ctx, B, T, workspace, workspace_bytes);
     if (s != EGTP_OK)
         return s;
+    if (want_p_hat && ctx->cfg.head_len.n_out < 2)
+        return EGTP_ERR_SHAPE;  // a scalar head has no distribution
     if (B == 0)
         return EGTP_OK;
-    if (!offsets_dev || !pooled_out || !lse_out || !pred_out || (T > 0 && !hidden))
+    if (!offsets_dev || !pooled_out || !lse_out || !pred_out || (T > 0 && !hidden) || (want_p_hat && !p_hat_out))
+        return EGTP_ERR_NULL;
+    if (T > 0 && lm_head_missing(ctx))
         return EGTP_ERR_NULL;
     if (offsets_host && (s = check_offsets_host(offsets_host, B, T)) != EGTP_OK)
         return s;
@@ -441,20 +489,24 @@ egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets
     a.state_scale = w.state_scale;
     a.partial = w.pool_part;
     EGTP_HIP(pool_entropy_weighted(a, st));
-    return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
+    return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, p_hat_out, st);
 }
 
-egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
-                     const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
-                     float *pooled_state, float *lse_state, void *workspace, size_t workspace_bytes,
-                     float *entropy_out, float *rem_pred_out, void *stream)
+egtp_status step_impl(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                      const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
+                      float *pooled_state, float *lse_state, void *workspace, size_t workspace_bytes,
+                      float *entropy_out, float *rem_pred_out, float *p_hat_out, bool want_p_hat, void *stream)
 {
     egtp_status s = check_common(ctx, B, T_new, workspace, workspace_bytes);
     if (s != EGTP_OK)
         return s;
+    if (want_p_hat && ctx->cfg.head_rem.n_out < 2)
+        return EGTP_ERR_SHAPE;
     if (B == 0)
         return EGTP_OK;
-    if (!pooled_state || !lse_state || !rem_pred_out || (T_new > 0 && !hidden_new))
+    if (!pooled_state || !lse_state || !rem_pred_out || (T_new > 0 && !hidden_new) || (want_p_hat && !p_hat_out))
+        return EGTP_ERR_NULL;
+    if (T_new > 0 && lm_head_missing(ctx))
         return EGTP_ERR_NULL;
     if (!offsets_new_dev) {
         if (T_new != B)
@@ -491,7 +543,47 @@ egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offse
     a.state_scale = w.state_scale;
     a.partial = w.pool_part;
     EGTP_HIP(pool_entropy_weighted(a, st));
-    return run_head(ctx, c.head_rem, pooled_state, slot_dev, B, w, rem_pred_out, st);
+    return run_head(ctx, c.head_rem, pooled_state, slot_dev, B, w, rem_pred_out, p_hat_out, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+egtp_status egtp_score(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                       const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
+                       size_t workspace_bytes, float *entropy_out, float *pooled_out, float *lse_out,
+                       float *pred_out, void *stream)
+{
+    return score_impl(ctx, hidden, offsets_dev, offsets_host, B, T, workspace, workspace_bytes, entropy_out,
+                      pooled_out, lse_out, pred_out, nullptr, false, stream);
+}
+
+egtp_status egtp_score_dist(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
+                            const int32_t *offsets_host, int32_t B, int64_t T, void *workspace,
+                            size_t workspace_bytes, float *entropy_out, float *pooled_out, float *lse_out,
+                            float *pred_out, float *p_hat_out, void *stream)
+{
+    return score_impl(ctx, hidden, offsets_dev, offsets_host, B, T, workspace, workspace_bytes, entropy_out,
+                      pooled_out, lse_out, pred_out, p_hat_out, true, stream);
+}
+
+egtp_status plp_step(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                     const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
+                     float *pooled_state, float *lse_state, void *workspace, size_t workspace_bytes,
+                     float *entropy_out, float *rem_pred_out, void *stream)
+{
+    return step_impl(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state,
+                     lse_state, workspace, workspace_bytes, entropy_out, rem_pred_out, nullptr, false, stream);
+}
+
+egtp_status plp_step_dist(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                          const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
+                          float *pooled_state, float *lse_state, void *workspace, size_t workspace_bytes,
+                          float *entropy_out, float *rem_pred_out, float *p_hat_out, void *stream)
+{
+    return step_impl(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state,
+                     lse_state, workspace, workspace_bytes, entropy_out, rem_pred_out, p_hat_out, true, stream);
 }
 
 egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
@@ -516,7 +608,7 @@ egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t 
     EGTP_HIP(pool_plain(hidden, c.dtype, c.d, offsets_dev, B, T, (int)kind, w.unit_start, w.pool_part, pooled_out,
                         st));
     if (pred_out)
-        return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, st);
+        return run_head(ctx, c.head_len, pooled_out, nullptr, B, w, pred_out, nullptr, st);
     return EGTP_OK;
 }
 
@@ -580,15 +672,15 @@ egtp_status egtp_head_train_step(const egtp_head_train *h, const float *x, const
         workspace_bytes < egtp_head_train_workspace_bytes(B, h->d, h->d_h, h->K))
         return EGTP_ERR_WORKSPACE;
     // the architecture check is remembered per device: this call is made once per training step
-    static int arch_ok_device = -1;
+    static DeviceMask arch_checked{0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess)
         return EGTP_ERR_ARCH;
-    if (dev != arch_ok_device) {
+    if (!device_bit_set(arch_checked, dev)) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess || strncmp(prop.gcnArchName, "gfx950", 6) != 0)
             return EGTP_ERR_ARCH;
-        arch_ok_device = dev;
+        set_device_bit(arch_checked, dev);
     }
 
     const TrainWorkspace w = carve_train(workspace, B, h->d, h->d_h, h->K);

@@ -54,7 +54,7 @@ constexpr int LOADS_PER_STEP = 2 * NPASS;
 constexpr int TB_GROUP = 8;    // token blocks that sweep the same vocabulary range together
 constexpr int XCDS = 8;            // workgroup i is placed on XCD i % 8
 constexpr int COHORT = 32;         // workgroups one XCD runs at a time (its compute units)
-constexpr int PACE_TILES = 4;      // vocabulary tiles between two pacing points
+constexpr int PACE_TILES = K1_PACE_TILES;  // vocabulary tiles between two pacing points
 constexpr int PACE_SPINS = 24;     // bound of one wait: polls of the counter ...
 constexpr int PACE_SLEEP = 4;      // ... each followed by a sleep of 64 * PACE_SLEEP cycles
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
@@ -436,7 +436,7 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
 {
     constexpr int NSTAGE = 4;
     constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    static unsigned long long lds_limit_raised = 0;
+    static DeviceMask lds_limit_raised{0};
     hipError_t ea = raise_dynamic_lds_limit((const void *)k1_entropy_bf16_kernel<NSTAGE>, LDS_BYTES, lds_limit_raised);
     if (ea != hipSuccess)
         return ea;
@@ -447,7 +447,7 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
         return hipErrorInvalidValue;
     const int kt = k_steps(d);
     // pacing counters: one per cohort, cleared by a kernel (a caller may be capturing a graph)
-    if (p.tiles_per_split <= PACE_TILES)
+    if (!k1_plan_paces(DT_BF16, p))
         pace = nullptr;  // no pacing point inside a range
     if (pace != nullptr) {
         const int n = XCDS * k1_pace_cohorts(units);

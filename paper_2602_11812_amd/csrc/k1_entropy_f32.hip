@@ -5,7 +5,7 @@
 // 4 x 4 logits per thread, K step 16.  As in the bf16 kernel the logits are folded into
 // per-token running statistics (m, S, U) as soon as a vocabulary tile is finished and are
 // never stored; the same merge kernel finishes H = ln S - U ln2 / S.
-#include "kernels.h"
+#include "k1_common.h"
 
 namespace egtp {
 namespace {
@@ -14,24 +14,6 @@ constexpr int TM = 64;   // vocabulary rows per tile
 constexpr int TN = 64;   // tokens per block
 constexpr int TK = 16;   // K step
 constexpr int PAD = 4;
-constexpr float NEG_BIG = -1.0e30f;
-constexpr float LOG2E = 1.4426950408889634f;
-
-struct Stats {
-    float m, S, U;
-};
-
-__device__ __forceinline__ Stats merge(Stats a, Stats b)
-{
-    float M = fmaxf(a.m, b.m);
-    float da = (a.m - M) * LOG2E, db = (b.m - M) * LOG2E;
-    float sa = __builtin_amdgcn_exp2f(da), sb = __builtin_amdgcn_exp2f(db);
-    Stats r;
-    r.m = M;
-    r.S = a.S * sa + b.S * sb;
-    r.U = (a.U + da * a.S) * sa + (b.U + db * b.S) * sb;
-    return r;
-}
 
 __global__ __launch_bounds__(256) void k1_entropy_f32_kernel(
     const float *__restrict__ W, const float *__restrict__ Hd, long T, int d, int V, int ntb,

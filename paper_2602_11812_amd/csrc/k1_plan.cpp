@@ -1,9 +1,6 @@
 // Launch geometry of the fused LM-head + entropy kernels (Eq. 2): how a batch of T tokens and a
 // vocabulary of V rows is cut into (token block, vocabulary range) workgroups.  Host code only.
-#include <stddef.h>
-#include <stdint.h>
-
-#include "kernels.h"
+#include "k1_plan.h"
 
 namespace egtp {
 

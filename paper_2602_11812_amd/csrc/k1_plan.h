@@ -1,0 +1,46 @@
+// Launch geometry of the fused LM-head + entropy kernels (Eq. 2).  Plain host arithmetic with no
+// dependency on the HIP runtime, so that it can also be compiled and checked on its own.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __HIPCC__
+#define EGTP_HOST_DEVICE __host__ __device__
+#else
+#define EGTP_HOST_DEVICE
+#endif
+
+namespace egtp {
+
+// Storage types of hidden states / weights (values match the public enum).
+enum : int { DT_F32 = 0, DT_BF16 = 1 };
+
+// Geometry of the fused LM-head + entropy kernel: tokens are cut into blocks of `tb_tokens`,
+// the vocabulary into `nsplit` ranges of `tiles_per_split` tiles of `tile_v` rows; each
+// (token block, vocabulary range) pair is one workgroup and leaves one partial (m, S, U)
+// triple per token.
+struct K1Plan {
+    int tb_tokens;        // tokens per block
+    int tile_v;           // vocabulary rows per tile
+    int ntb;              // token blocks
+    int ntiles_v;         // vocabulary tiles in total
+    int nsplit;           // vocabulary ranges
+    int tiles_per_split;  // tiles per range (last range may hold fewer)
+};
+
+K1Plan k1_plan(int dtype, int64_t T, int d, int V);
+// floats needed for the partial triples of a plan (3 * nsplit * T)
+size_t k1_partial_floats(const K1Plan &p, int64_t T);
+// upper bound of k1_partial_floats over every T' <= T
+size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
+// The bf16 kernel paces the workgroups that share an XCD with one counter per cohort of 32:
+// cohorts per XCD for a grid of `units` workgroups, and ints to reserve for every T' <= T.
+EGTP_HOST_DEVICE inline int k1_pace_cohorts(long units) { return (int)(((units + 7) / 8 + 31) / 32); }
+size_t k1_pace_ints_bound(int dtype, int64_t T, int d, int V);
+
+// A range of the bf16 kernel has a pacing point after every K1_PACE_TILES vocabulary tiles, so only
+// ranges longer than that pace at all.
+constexpr int K1_PACE_TILES = 4;
+inline bool k1_plan_paces(int dtype, const K1Plan &p) { return dtype == DT_BF16 && p.tiles_per_split > K1_PACE_TILES; }
+
+}  // namespace egtp

@@ -7,6 +7,7 @@
 // partial weighted sum (already normalised with the sequence's final log-sum-exp), and a
 // finalize kernel adds a sequence's partials in unit order.  No atomics: bit-reproducible.
 #include "kernels.h"
+#include "wave_reduce.h"
 
 namespace egtp {
 namespace {
@@ -14,20 +15,6 @@ namespace {
 constexpr float NEG_INF = -__builtin_inff();
 
 // ---- block reductions (256 threads), fixed tree => deterministic ---------------------
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v += __shfl_xor(v, o);
-    return v;
-}
 __device__ float block_max(float v, float *sh)
 {
     v = wave_max(v);
@@ -68,7 +55,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const int32_t *__restrict__ i
         if (b < B) {
             if (UNITS) {
                 const int n = in[b + 1] - in[b];
-                v = (n + POOL_UNIT - 1) / POOL_UNIT;
+                v = n > 0 ? (n + POOL_UNIT - 1) / POOL_UNIT : 0;
             } else {
                 v = in[b];
             }
@@ -113,9 +100,13 @@ __global__ __launch_bounds__(256) void seg_ids_kernel(const int32_t *__restrict_
     seg[t] = (B > 0 && t < offsets[B]) ? find_segment(offsets, B, t) : -1;
 }
 
+// Device offsets are the caller's: whatever they hold, no token index leaves [0, T] and no unit
+// index leaves the partial buffer (a malformed table gives wrong numbers, not wild accesses).
+__device__ __forceinline__ long clamp_token(long t, long T) { return t < 0 ? 0 : (t > T ? T : t); }
+
 // ---- Eq. 3: per-sequence log-sum-exp of H/alpha, joined with the old state's lse ---------
 __global__ __launch_bounds__(256) void pool_lse_kernel(const float *__restrict__ entropy,
-                                                       const int32_t *__restrict__ offsets,
+                                                       const int32_t *__restrict__ offsets, long T,
                                                        const int32_t *__restrict__ slot, float inv_alpha,
                                                        const float *__restrict__ state_lse,
                                                        float *__restrict__ lse_new,
@@ -123,7 +114,7 @@ __global__ __launch_bounds__(256) void pool_lse_kernel(const float *__restrict__
 {
     __shared__ float sh[4];
     const int b = blockIdx.x;
-    const int lo = offsets[b], hi = offsets[b + 1];
+    const int lo = (int)clamp_token(offsets[b], T), hi = (int)clamp_token(offsets[b + 1], T);
     const int s = slot ? slot[b] : b;
     const float L_old = state_lse ? state_lse[s] : NEG_INF;
     float mx = NEG_INF;
@@ -173,16 +164,16 @@ __device__ __forceinline__ void widen16(const uint4 &q, float (&h)[BF16 ? 8 : 4]
 template <bool BF16, int MODE>
 __global__ __launch_bounds__(256) void pool_partial_kernel(
     const void *__restrict__ hidden, int d, const float *__restrict__ entropy,
-    const int32_t *__restrict__ offsets, int32_t B, float inv_alpha, const float *__restrict__ lse_new,
+    const int32_t *__restrict__ offsets, int32_t B, long T, float inv_alpha, const float *__restrict__ lse_new,
     const int32_t *__restrict__ unit_start, float *__restrict__ partial)
 {
     __shared__ float w[POOL_UNIT];
-    const int u = blockIdx.x;
+    const int u = blockIdx.x;  // the grid is pool_units_bound(T, B): u indexes inside the partial buffer
     if (u >= unit_start[B])
         return;
     const int b = find_segment(unit_start, B, u);
-    const long t0 = (long)offsets[b] + (long)(u - unit_start[b]) * POOL_UNIT;
-    const int n = (int)min((long)POOL_UNIT, (long)offsets[b + 1] - t0);
+    const long t0 = clamp_token((long)offsets[b] + (long)(u - unit_start[b]) * POOL_UNIT, T);
+    const int n = (int)max(0L, min((long)POOL_UNIT, clamp_token(offsets[b + 1], T) - t0));
     if (MODE == POOL_WEIGHTED) {
         if (threadIdx.x < POOL_UNIT)
             w[threadIdx.x] = threadIdx.x < n ? __expf(entropy[t0 + threadIdx.x] * inv_alpha - lse_new[b]) : 0.f;
@@ -232,13 +223,13 @@ template <int MODE>
 __global__ __launch_bounds__(256) void pool_finalize_plain_kernel(const float *__restrict__ partial,
                                                                   const int32_t *__restrict__ unit_start,
                                                                   const int32_t *__restrict__ offsets, int d,
-                                                                  float *__restrict__ out_pooled)
+                                                                  int units_cap, float *__restrict__ out_pooled)
 {
     const int b = blockIdx.x;
     const int k = blockIdx.y * 256 + threadIdx.x;
     if (k >= d)
         return;
-    const int u0 = unit_start[b], u1 = unit_start[b + 1];
+    const int u0 = unit_start[b], u1 = min(unit_start[b + 1], units_cap);
     const int len = offsets[b + 1] - offsets[b];
     float r = (MODE == POOL_MAXIMUM && len > 0) ? NEG_INF : 0.f;  // an empty sequence pools to zero
     for (int u = u0; u < u1; ++u) {
@@ -253,7 +244,7 @@ __global__ __launch_bounds__(256) void pool_finalize_plain_kernel(const float *_
 // ---- sum a sequence's partials in unit order, add the rescaled old state ------------------
 __global__ __launch_bounds__(256) void pool_finalize_kernel(
     const float *__restrict__ partial, const int32_t *__restrict__ unit_start,
-    const int32_t *__restrict__ slot, int d, const float *state_pooled,
+    const int32_t *__restrict__ slot, int d, int units_cap, const float *state_pooled,
     const float *__restrict__ state_scale, const float *__restrict__ lse_new, float *out_pooled,
     float *out_lse)
 {
@@ -261,7 +252,7 @@ __global__ __launch_bounds__(256) void pool_finalize_kernel(
     const int k = blockIdx.y * 256 + threadIdx.x;
     const int s = slot ? slot[b] : b;
     if (k < d) {
-        const int u0 = unit_start[b], u1 = unit_start[b + 1];
+        const int u0 = unit_start[b], u1 = min(unit_start[b + 1], units_cap);
         float sum = 0.f;
         for (int u = u0; u < u1; ++u)
             sum += partial[(long)u * d + k];
@@ -331,7 +322,7 @@ __global__ __launch_bounds__(256) void plp_fold1_kernel(const void *__restrict__
 // ---- Table 3 alternative: the last token's hidden state ------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void pool_last_kernel(const void *__restrict__ hidden, int d,
-                                                        const int32_t *__restrict__ offsets,
+                                                        const int32_t *__restrict__ offsets, long T,
                                                         float *__restrict__ out_pooled)
 {
     constexpr int VEC = BF16 ? 8 : 4;
@@ -339,7 +330,7 @@ __global__ __launch_bounds__(256) void pool_last_kernel(const void *__restrict__
     const int c = blockIdx.y * 256 + threadIdx.x;
     if (c * VEC >= d)
         return;
-    const long lo = offsets[b], hi = offsets[b + 1];
+    const long lo = clamp_token(offsets[b], T), hi = clamp_token(offsets[b + 1], T);
     float h[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e)
@@ -385,19 +376,19 @@ hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
         return hipGetLastError();
     }
     hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(256), 0, st, a.offsets, a.B, a.unit_start);
-    hipLaunchKernelGGL(pool_lse_kernel, dim3(a.B), dim3(256), 0, st, a.entropy, a.offsets, a.slot,
+    hipLaunchKernelGGL(pool_lse_kernel, dim3(a.B), dim3(256), 0, st, a.entropy, a.offsets, (long)a.T, a.slot,
                        a.inv_alpha, a.state_lse, a.lse_new, a.state_scale);
     const long units = pool_units_bound(a.T, a.B);
     if (units > 0x7fffffffL)
         return hipErrorInvalidValue;
     if (bf16)
         hipLaunchKernelGGL((pool_partial_kernel<true, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
-                           a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
+                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
     else
         hipLaunchKernelGGL((pool_partial_kernel<false, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
-                           a.d, a.entropy, a.offsets, a.B, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
+                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
     hipLaunchKernelGGL(pool_finalize_kernel, dim3(a.B, (a.d + 255) / 256), dim3(256), 0, st, a.partial,
-                       a.unit_start, a.slot, a.d, a.state_pooled, a.state_scale, a.lse_new, a.out_pooled,
+                       a.unit_start, a.slot, a.d, (int)units, a.state_pooled, a.state_scale, a.lse_new, a.out_pooled,
                        a.out_lse);
     return hipGetLastError();
 }
@@ -412,9 +403,11 @@ hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offse
         const int vec = bf16 ? 8 : 4;
         const dim3 grid(B, (d / vec + 255) / 256);
         if (bf16)
-            hipLaunchKernelGGL(pool_last_kernel<true>, grid, dim3(256), 0, st, hidden, d, offsets, out_pooled);
+            hipLaunchKernelGGL(pool_last_kernel<true>, grid, dim3(256), 0, st, hidden, d, offsets, (long)T,
+                               out_pooled);
         else
-            hipLaunchKernelGGL(pool_last_kernel<false>, grid, dim3(256), 0, st, hidden, d, offsets, out_pooled);
+            hipLaunchKernelGGL(pool_last_kernel<false>, grid, dim3(256), 0, st, hidden, d, offsets, (long)T,
+                               out_pooled);
         return hipGetLastError();
     }
     // average and maximum stream every token once: same units of <= POOL_UNIT tokens as Eq. 4
@@ -426,9 +419,9 @@ hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offse
 #define EGTP_POOL_PLAIN(BF, MODE)                                                                          \
     do {                                                                                                   \
         hipLaunchKernelGGL((pool_partial_kernel<BF, MODE>), dim3((unsigned)units), dim3(256), 0, st, hidden, \
-                           d, nullptr, offsets, B, 0.f, nullptr, unit_start, partial);                     \
+                           d, nullptr, offsets, B, (long)T, 0.f, nullptr, unit_start, partial);            \
         hipLaunchKernelGGL(pool_finalize_plain_kernel<MODE>, fgrid, dim3(256), 0, st, partial, unit_start, \
-                           offsets, d, out_pooled);                                                        \
+                           offsets, d, (int)units, out_pooled);                                            \
     } while (0)
     if (kind == 0) {
         if (bf16)

@@ -15,6 +15,7 @@
 // would, in fp32.  Fragments come straight from global memory: a lane's 8 K-elements are 16
 // contiguous bytes of a weight row and 32 contiguous bytes of a pooled row.
 #include "kernels.h"
+#include "wave_reduce.h"
 
 namespace egtp {
 namespace {
@@ -284,14 +285,6 @@ __global__ __launch_bounds__(256) void head_layer1_mfma_kernel(const float *__re
     }
 }
 
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v += __shfl_xor(v, o);
-    return v;
-}
-
 // one workgroup (4 waves) per sequence: out[o] = b2[o] + w2[o,:] . act[b,:]; n_out > 1 => Eq. 6
 // LDS: a[d_h] | partial[4][n_out]
 template <bool WBF16>
@@ -300,7 +293,8 @@ __global__ __launch_bounds__(256) void head_layer2_kernel(const float *__restric
                                                           const void *__restrict__ w2,
                                                           const float *__restrict__ b2,
                                                           const float *__restrict__ centers,
-                                                          float *__restrict__ pred)
+                                                          float *__restrict__ pred,
+                                                          float *__restrict__ p_hat)
 {
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -353,6 +347,15 @@ __global__ __launch_bounds__(256) void head_layer2_kernel(const float *__restric
     }
     if (lane == 0)
         pred[b] = n_out == 1 ? y : num / den;
+    // the distribution itself (Eq. 6's p-hat), when the caller wants it: bin o by lane o % 64
+    if (p_hat != nullptr && n_out > 1) {
+        const float inv = 1.0f / den;
+        for (int o = lane; o < n_out; o += 64) {
+            const float s = ((partial[o] + partial[n_out + o]) + (partial[2 * n_out + o] + partial[3 * n_out + o])) +
+                            (b2 ? b2[o] : 0.f);
+            p_hat[(long)b * n_out + o] = __expf(s - m) * inv;
+        }
+    }
 }
 
 }  // namespace
@@ -418,7 +421,7 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
     const size_t lds2 = ((size_t)a.d_h + 4 * (size_t)a.n_out) * sizeof(float);
     if (lds2 > 96 * 1024)
         return hipErrorInvalidValue;
-    static unsigned long long raised_bf16 = 0, raised_f32 = 0;
+    static DeviceMask raised_bf16{0}, raised_f32{0};
     hipError_t e1 = raise_dynamic_lds_limit((const void *)head_layer2_kernel<true>, 96 * 1024, raised_bf16);
     hipError_t e2 = raise_dynamic_lds_limit((const void *)head_layer2_kernel<false>, 96 * 1024, raised_f32);
     if (e1 != hipSuccess || e2 != hipSuccess)
@@ -428,10 +431,10 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
         return e;
     if (a.wdtype == DT_BF16)
         hipLaunchKernelGGL(head_layer2_kernel<true>, dim3(a.B), dim3(256), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
-                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
+                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred, a.p_hat);
     else
         hipLaunchKernelGGL(head_layer2_kernel<false>, dim3(a.B), dim3(256), lds2, st, a.act, nks, a.B, a.b1, a.d_h,
-                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred);
+                           a.n_out, a.w2, a.b2, a.bin_centers, a.pred, a.p_hat);
     return hipGetLastError();
 }
 

@@ -16,25 +16,10 @@
 //   5. loss                fixed-order sum of the per-sample terms
 // No floating-point atomics anywhere: results are bit-reproducible.
 #include "kernels.h"
+#include "wave_reduce.h"
 
 namespace egtp {
 namespace {
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v += __shfl_xor(v, o);
-    return v;
-}
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
 
 struct Adam {
     float lr, beta1, beta2, omb1, omb2, eps, wd, corr1, corr2;
@@ -291,7 +276,7 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     const size_t lds = ((size_t)a.d_h + 2 * (size_t)a.K) * sizeof(float);
     if (lds > 96 * 1024)
         return hipErrorInvalidValue;
-    static unsigned long long lds_limit_raised = 0;
+    static DeviceMask lds_limit_raised{0};
     hipError_t ea = raise_dynamic_lds_limit((const void *)train_sample_kernel, 96 * 1024, lds_limit_raised);
     if (ea != hipSuccess)
         return ea;

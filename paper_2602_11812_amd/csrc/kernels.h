@@ -4,49 +4,40 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
+#include "k1_plan.h"
+
 namespace egtp {
 
-// Raises a kernel's dynamic LDS limit once per device: `done` is the caller's bit mask of the
-// devices it has been raised on (a race between two first calls only repeats the setting).
-inline hipError_t raise_dynamic_lds_limit(const void *kernel, int bytes, unsigned long long &done)
+// One bit per device, set once something has been done for that device.  Shared by every context
+// and thread of the process, hence atomic; two first calls that race only repeat the action.
+using DeviceMask = std::atomic<unsigned long long>;
+inline bool device_bit_set(const DeviceMask &m, int dev)
+{
+    return dev >= 0 && dev < 64 && ((m.load(std::memory_order_acquire) >> dev) & 1ull);
+}
+inline void set_device_bit(DeviceMask &m, int dev)
+{
+    if (dev >= 0 && dev < 64)
+        m.fetch_or(1ull << dev, std::memory_order_release);
+}
+
+// Raises a kernel's dynamic LDS limit once per device; `done` is the caller's mask of the devices
+// it has been raised on.
+inline hipError_t raise_dynamic_lds_limit(const void *kernel, int bytes, DeviceMask &done)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
         return e;
-    if (dev >= 0 && dev < 64 && ((done >> dev) & 1ull))
+    if (device_bit_set(done, dev))
         return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64)
-        done |= 1ull << dev;
+    if (e == hipSuccess)
+        set_device_bit(done, dev);
     return e;
 }
-
-// Storage types of hidden states / weights (values match the public enum).
-enum : int { DT_F32 = 0, DT_BF16 = 1 };
-
-// Geometry of the fused LM-head + entropy kernel: tokens are cut into blocks of `tb_tokens`,
-// the vocabulary into `nsplit` ranges of `tiles_per_split` tiles of `tile_v` rows; each
-// (token block, vocabulary range) pair is one workgroup and leaves one partial (m, S, U)
-// triple per token.
-struct K1Plan {
-    int tb_tokens;        // tokens per block
-    int tile_v;           // vocabulary rows per tile
-    int ntb;              // token blocks
-    int ntiles_v;         // vocabulary tiles in total
-    int nsplit;           // vocabulary ranges
-    int tiles_per_split;  // tiles per range (last range may hold fewer)
-};
-
-K1Plan k1_plan(int dtype, int64_t T, int d, int V);
-// floats needed for the partial triples of a plan (3 * nsplit * T)
-size_t k1_partial_floats(const K1Plan &p, int64_t T);
-// upper bound of k1_partial_floats over every T' <= T
-size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
-// The bf16 kernel paces the workgroups that share an XCD with one counter per cohort of 32:
-// cohorts per XCD for a grid of `units` workgroups, and ints to reserve for every T' <= T.
-__host__ __device__ inline int k1_pace_cohorts(long units) { return (int)(((units + 7) / 8 + 31) / 32); }
-size_t k1_pace_ints_bound(int dtype, int64_t T, int d, int V);
 
 // Packed operand layout of the bf16 matrix-core kernel: blocks of 256 rows x K1_PACK_K
 // elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * steps + step with
@@ -115,6 +106,7 @@ struct HeadArgs {
     const float *bin_centers; // [n_out] when n_out > 1
     float *act;               // workspace, head_act_floats_bound(d, d_h, B) floats: partial pre-activations
     float *pred;              // [B]
+    float *p_hat;             // [B x n_out] softmax over the bins (Eq. 6), or NULL; n_out > 1 only
 };
 // Number of partial pre-activation planes layer 1 leaves: it is split along d so that about a
 // thousand workgroups exist whatever the batch (a small batch gets many thin slices).

@@ -26,13 +26,60 @@ def gpu():
     return binding
 
 
-def _score_full(gpu, w):
+def _poison(sc, T, B):
+    """Fill the scorer's workspace with NaN bit patterns: nothing a call reads may be left over from before."""
+    import torch
+    sc.workspace(T, B).view(torch.int32).fill_(0x7FC00000)
+
+
+def _score_full(gpu, w, twice=False):
+    """Scores the whole workload on a NaN-poisoned workspace; `twice`: a second time, which has to reproduce
+    every output bit for bit (no atomics-order or race dependence, nothing read before it is written)."""
     import torch
     td = gpu.to_device
     sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
     off = sc.build_offsets(torch.from_numpy(w.lengths).cuda(), w.T)
-    out = {k: v.cpu().numpy() for k, v in sc.score(td(w.hidden), off).items()}
+    hidden = td(w.hidden)
+    _poison(sc, w.T, w.spec.B)
+    out = {k: v.cpu().numpy() for k, v in sc.score(hidden, off).items()}
+    if twice:
+        _poison(sc, w.T, w.spec.B)
+        again = {k: v.cpu().numpy() for k, v in sc.score(hidden, off).items()}
+        for k in out:
+            assert np.array_equal(out[k].view(np.int32), again[k].view(np.int32)), f"{k} differs between two runs"
     return sc, off.cpu().numpy(), out
+
+
+def _block_edge_tokens(T):
+    """Tokens at the seams of the fused kernel's tiling: the 256-token block edges, the 128-token wave halves
+    inside a block, the 16-token fragment edges, and the ragged last block."""
+    last0 = (T - 1) // 256 * 256
+    toks = [0, 15, 16, 127, 128, 129, 255, 256, 257, 383, 384, 2047, 2048, last0 - 1, last0, last0 + 1, T - 2, T - 1]
+    return [t for t in toks if 0 <= t < T]
+
+
+def _check_gaussian_logit_statistic(w, entropy):
+    """Every token against the closed form of this input recipe.  The logits of a token are (nearly) independent
+    Gaussians of variance s2 = |h|^2 / d, for which H = ln V - s2 / 2 up to the sampling noise of a V-term sum
+    of log-normals: simulated at V = 151936 its standard deviation is 0.003 nat at s2 = 1, 0.012 at s2 = 2,
+    0.06 with heavy tails at s2 = 4 (V = 32000: about twice that).  So the tight bar (0.1 nat) is applied where
+    s2 <= 2, a gross one (1 nat) everywhere, and the mean gap of every 256-token block has to stay below 0.03
+    (a vocabulary range that went missing for a block shifts all its tokens by ln(17/18) = -0.057)."""
+    lnV = math.log(w.spec.V)
+    s2 = np.empty(w.T)
+    for t0 in range(0, w.T, 8192):
+        h = w.hidden[t0:t0 + 8192]
+        h = wl.bf16_bits_to_f32(h) if h.dtype == np.uint16 else h
+        s2[t0:t0 + 8192] = np.einsum("ij,ij->i", h, h, dtype=np.float64) / w.spec.d
+    gap = entropy.astype(np.float64) - (lnV - s2 / 2.0)
+    calm = s2 <= 2.0
+    assert calm.sum() > w.T // 3
+    assert np.abs(gap[calm]).max() <= 0.1, f"gap {np.abs(gap[calm]).max()} at token {np.nonzero(calm)[0][np.abs(gap[calm]).argmax()]}"
+    assert np.abs(gap).max() <= 1.0, f"gap {np.abs(gap).max()} at token {np.abs(gap).argmax()}"
+    if w.spec.V >= 100000:
+        nb = w.T // 256
+        block_mean = gap[:nb * 256].reshape(nb, 256).mean(axis=1)
+        assert np.abs(block_mean).max() <= 0.03, f"block {np.abs(block_mean).argmax()} mean gap {np.abs(block_mean).max()}"
 
 
 def _check_sampled(w, off, out, n_seq_sampled, n_short):
@@ -48,7 +95,7 @@ def _check_sampled(w, off, out, n_seq_sampled, n_short):
     for b in seqs:
         lo, hi = int(ooff[b]), int(ooff[b + 1])
         toks += [lo, hi - 1] + rng.integers(lo, hi, size=2).tolist()
-    toks = np.unique(np.asarray(toks))
+    toks = np.unique(np.asarray(toks + _block_edge_tokens(w.T)))
     H = oracle.entropy(np.ascontiguousarray(w.hidden[toks]), w.w_lm)
     err = np.abs(out["entropy"][toks].astype(np.float64) - H)
     assert err.max() <= TOL_ENTROPY_ABS, f"sampled entropy err {err.max()}"
@@ -71,6 +118,7 @@ def _check_sampled(w, off, out, n_seq_sampled, n_short):
     assert_pred_close(out["pred"], oracle.predict(pooled, head))
 
     # properties that hold at any size
+    _check_gaussian_logit_statistic(w, out["entropy"])
     lnV = math.log(w.spec.V)
     assert np.all(out["entropy"] > 0) and np.all(out["entropy"] <= lnV + 1e-4)
     n = w.lengths.astype(np.float64)
@@ -80,7 +128,9 @@ def _check_sampled(w, off, out, n_seq_sampled, n_short):
 def test_serving_workload_full_size(gpu):
     w = wl.make(wl.SPECS["serving"])
     assert w.T == 137720 and w.spec.V == 151936 and w.spec.d == 4096
-    sc, off, out = _score_full(gpu, w)
+    plan = gpu.egtp_launch_plan_query(gpu.EGTP_BF16, w.spec.d, w.spec.V, w.T)
+    assert plan.paced == 1 and plan.tiles_per_range >= 5     # the multi-tile, paced sweep the benchmark times
+    sc, off, out = _score_full(gpu, w, twice=True)
     _check_sampled(w, off, out, n_seq_sampled=24, n_short=2)
     sc.close()
 
@@ -132,6 +182,55 @@ def test_plp_decode_full_batch(gpu):
     sc.close()
 
 
+def test_plp_256_steps_checkpoint_and_resume(gpu):
+    """The decode workload in full: 512 sequences, 256 consecutive steps from the empty state.  The state is the
+    caller's (pooled, lse) pair, so copying it out after step 128 and back in IS the checkpoint: the resumed run
+    has to reproduce the uninterrupted one bit for bit.  Sampled sequences at step 256 against the oracle's
+    recompute over their 256 generated tokens."""
+    import torch
+    spec = wl.SPECS["plp_decode"]
+    w = wl.make(spec)
+    td = gpu.to_device
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)))
+    B, d, steps = spec.B, spec.d, 256
+    pick = np.array([0, 201, 511])
+    kept = np.empty((steps, len(pick), d), dtype=np.uint16)
+
+    def run(t0, t1, pooled, lse, keep=False):
+        pred = None
+        for t in range(t0, t1):
+            g = wl.decode_hidden(spec, t + 1)
+            if keep:
+                kept[t] = g[pick]
+            pred = sc.step(td(g), pooled, lse)
+        return pred
+
+    pooled = torch.zeros(B, d, dtype=torch.float32, device="cuda")
+    lse = torch.full((B,), -math.inf, dtype=torch.float32, device="cuda")
+    pred_a = run(0, steps, pooled, lse, keep=True).cpu().numpy()
+
+    p1 = torch.zeros(B, d, dtype=torch.float32, device="cuda")
+    l1 = torch.full((B,), -math.inf, dtype=torch.float32, device="cuda")
+    run(0, 128, p1, l1)
+    ckpt = (p1.cpu().numpy().copy(), l1.cpu().numpy().copy())            # copy-out ...
+    del p1, l1
+    p2, l2 = torch.from_numpy(ckpt[0]).cuda(), torch.from_numpy(ckpt[1]).cuda()   # ... and back in
+    pred_b = run(128, steps, p2, l2).cpu().numpy()
+    assert torch.equal(p2, pooled) and torch.equal(l2, lse)
+    assert np.array_equal(pred_a.view(np.int32), pred_b.view(np.int32))
+
+    hist = np.ascontiguousarray(kept.transpose(1, 0, 2).reshape(len(pick) * steps, d))   # sequence-major
+    want = oracle.egtp(hist, np.arange(len(pick) + 1, dtype=np.int32) * steps, w.w_lm, oracle.Head(w.w1, w.w2))
+    pooled_np, lse_np = pooled.cpu().numpy(), lse.cpu().numpy()
+    for i, b in enumerate(pick):
+        assert rel_l2(pooled_np[b], want.pooled[i]) <= TOL_POOLED_REL_L2
+        assert abs(lse_np[b] - want.lse[i]) <= TOL_LSE_ABS
+    # predictions of the sampled sequences on the scale of the whole batch's predictions
+    floor = math.sqrt(float(np.mean(pred_a.astype(np.float64) ** 2)))
+    assert np.all(np.abs(pred_a[pick] - want.pred) <= 1e-2 * np.maximum(np.abs(want.pred), floor))
+    sc.close()
+
+
 def test_rl_one_to_many_sampling(gpu):
     # 64 prompts x 16 samples (1024 state slots), d = 5120, V = 151936: EGTP on the prompts, the
     # state copied to every sample's slot, then two ragged PLP folds of 64 freshly generated
@@ -146,6 +245,13 @@ def test_rl_one_to_many_sampling(gpu):
     out = sc.score(td(w.hidden), off)
     ooff = oracle.offsets_from_lengths(w.lengths)
     prompt_ent = out["entropy"].cpu().numpy().astype(np.float64)
+    # the prompt pass runs several vocabulary tiles per workgroup at d = 5120: sampled tokens against the oracle,
+    # every token against the closed-form statistic
+    ptoks = np.unique(np.concatenate([np.random.default_rng(11).choice(w.T, size=10, replace=False),
+                                      _block_edge_tokens(w.T)[-6:]]))
+    Hp = oracle.entropy(np.ascontiguousarray(w.hidden[ptoks]), w.w_lm)
+    assert np.abs(prompt_ent[ptoks] - Hp).max() <= TOL_ENTROPY_ABS
+    _check_gaussian_logit_statistic(w, prompt_ent)
 
     pooled = out["pooled"].repeat_interleave(S_PER, dim=0).contiguous()      # slot = prompt * 16 + sample
     lse = out["lse"].repeat_interleave(S_PER, dim=0).contiguous()

@@ -200,6 +200,147 @@ def test_head_maximum_sizes(gpu):
     sc.close()
 
 
+@pytest.mark.parametrize("storage", ["bf16", "f32"])
+def test_k_bin_head_hands_out_its_distribution(gpu, storage):
+    """Eq. 6: the scoring calls of a K-bin head also return p-hat, the softmax the predicted length is the
+    expectation of -- element by element against the oracle, rows summing to 1, for EGTP and for a PLP step."""
+    import torch
+    K, d_h, d = 20, 48, 64
+    w = _small_bf16(seed=149, B=5, d=d, V=300, d_h=d_h, lengths=(9, 1, 40, 0, 17))
+    rng = np.random.default_rng(3)
+    w2f = (rng.normal(0, 2.0, size=(K, d_h)) / np.sqrt(d_h)).astype(np.float32)
+    b1 = (0.05 * rng.normal(size=d_h)).astype(np.float32)
+    b2 = rng.normal(size=K).astype(np.float32)
+    centers = np.linspace(16.0, 4096.0, K).astype(np.float32)
+    td = gpu.to_device
+    if storage == "bf16":
+        w1s, w2s = w.w1, wl.to_bf16_bits(w2f)
+    else:
+        w1s, w2s = wl.bf16_bits_to_f32(w.w1), w2f
+    head_dev = gpu.make_head(td(w1s), td(w2s), td(b1), td(b2), td(centers))
+    sc = gpu.Scorer(td(w.w_lm), head_dev)
+    off = _offsets_on_gpu(gpu, sc, w.lengths)
+    B, T = w.spec.B, w.T
+    out = dict(entropy=torch.empty(T, device="cuda"), pooled=torch.empty(B, d, device="cuda"),
+               lse=torch.empty(B, device="cuda"), pred=torch.empty(B, device="cuda"))
+    p_hat = torch.full((B, K), float("nan"), device="cuda")
+    gpu.egtp_score_dist(sc.ctx, td(w.hidden), off, None, B, T, sc.workspace(T, B), out["entropy"], out["pooled"],
+                        out["lse"], out["pred"], p_hat)
+    head = oracle.Head(w1s, w2s, b1, b2, centers.astype(np.float64))
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, head)
+    want_p, want_y = oracle.bin_decode(oracle.head_raw(want.pooled, head), centers)
+    got_p = p_hat.cpu().numpy().astype(np.float64)
+    assert np.abs(got_p - want_p).max() <= 2e-4 and np.abs(got_p.sum(axis=1) - 1.0).max() <= 1e-5
+    assert_egtp_close(_np(out), want)
+    assert np.abs(got_p @ centers.astype(np.float64) - out["pred"].cpu().numpy()).max() <= 1e-3 * centers.max()
+    # one PLP step: the remaining-length head (the same one here) and its distribution
+    g = wl.decode_hidden(w.spec, 1)
+    pooled, lse = out["pooled"].clone(), out["lse"].clone()
+    rem, p_rem = torch.empty(B, device="cuda"), torch.full((B, K), float("nan"), device="cuda")
+    gpu.plp_step_dist(sc.ctx, td(g), None, None, None, B, B, pooled, lse, sc.workspace(B, B), None, rem, p_rem)
+    r = oracle.plp(w.hidden, oracle.offsets_from_lengths(w.lengths), [g], w.w_lm, head)[0]
+    rp, _ = oracle.bin_decode(oracle.head_raw(r.pooled, head), centers)
+    assert np.abs(p_rem.cpu().numpy() - rp).max() <= 2e-4
+    assert_pred_close(rem.cpu().numpy(), r.pred)
+    sc.close()
+    # a scalar head has no distribution: refused before anything is launched
+    sc1 = _scorer(gpu, w)
+    with pytest.raises(gpu.EgtpError) as e:
+        gpu.egtp_score_dist(sc1.ctx, td(w.hidden), off, None, B, T, sc1.workspace(T, B), out["entropy"], out["pooled"],
+                            out["lse"], out["pred"], p_hat)
+    assert e.value.status == 2
+    sc1.close()
+
+
+def test_two_heads_of_unequal_width_share_the_workspace(gpu):
+    """fp32 storage, head_len wider than head_rem (4096 against 4032 rows: the narrower head is cut into more
+    slices along d and needs MORE partial planes).  The workspace is exactly egtp_workspace_bytes with a guard
+    band behind it that no call may touch; both heads against the oracle."""
+    import torch
+    d, V, B = 320, 300, 3                      # d / 16 = 20 slices possible: 17 (4032 rows) against 16 (4096 rows)
+    spec = wl.scaled(wl.SPECS["tiny"], seed=151, B=B, d=d, V=V, d_h=4096, lengths=(5, 1, 9))
+    w = wl.make(spec)
+    rng = np.random.default_rng(5)
+    rem_w1 = rng.normal(0, d ** -0.5, size=(4032, d)).astype(np.float32)
+    rem_w2 = rng.normal(0, 4032 ** -0.5, size=(1, 4032)).astype(np.float32)
+    td = gpu.to_device
+    sc = gpu.Scorer(td(w.w_lm), gpu.make_head(td(w.w1), td(w.w2)), gpu.make_head(td(rem_w1), td(rem_w2)))
+    need = gpu.egtp_workspace_bytes(sc.ctx, w.T, B)
+    GUARD = 1 << 20
+    buf = torch.full((need + GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = _offsets_on_gpu(gpu, sc, w.lengths)
+    out = dict(entropy=torch.empty(w.T, device="cuda"), pooled=torch.empty(B, d, device="cuda"),
+               lse=torch.empty(B, device="cuda"), pred=torch.empty(B, device="cuda"))
+    gpu.egtp_score(sc.ctx, td(w.hidden), off, None, B, w.T, buf[:need], out["entropy"], out["pooled"], out["lse"],
+                   out["pred"])
+    g = wl.decode_hidden(spec, 1)
+    pooled, lse, rem = out["pooled"].clone(), out["lse"].clone(), torch.empty(B, device="cuda")
+    gpu.plp_step(sc.ctx, td(g), None, None, None, B, B, pooled, lse, buf[:need], None, rem)
+    torch.cuda.synchronize()
+    assert bool((buf[need:] == 0x5A).all()), "a call wrote behind its workspace"
+    ooff = oracle.offsets_from_lengths(w.lengths)
+    assert_egtp_close(_np(out), oracle.egtp(w.hidden, ooff, w.w_lm, oracle.Head(w.w1, w.w2)))
+    r = oracle.plp(w.hidden, ooff, [g], w.w_lm, oracle.Head(rem_w1, rem_w2))[0]
+    assert_pred_close(rem.cpu().numpy(), r.pred)
+    sc.close()
+
+
+def test_context_on_a_packed_lm_head_alone(gpu):
+    """A bf16 context needs no row-major W_lm once a packed copy exists: pack with one context, free the
+    original, adopt the packed copy in a context created with w_lm = NULL -- same bits out."""
+    import torch
+    w = _small_bf16(seed=157, B=3, d=96, V=700, d_h=16, lengths=(30, 300, 2))
+    td = gpu.to_device
+    w_lm_dev = td(w.w_lm)
+    a = gpu.Scorer(w_lm_dev, gpu.make_head(td(w.w1), td(w.w2)))
+    off = _offsets_on_gpu(gpu, a, w.lengths)
+    ref = _np(a.score(td(w.hidden), off))
+    packed = a._w_packed
+    cfg = gpu.egtp_config()
+    cfg.vocab, cfg.d, cfg.dtype, cfg.w_lm, cfg.alpha = w.spec.V, w.spec.d, gpu.EGTP_BF16, None, 1.0
+    cfg.head_len = gpu.make_head(td(w.w1), td(w.w2))
+    ctx = gpu.egtp_create(cfg)
+    B, T, d = w.spec.B, w.T, w.spec.d
+    out = [torch.empty(T, device="cuda"), torch.empty(B, d, device="cuda"), torch.empty(B, device="cuda"),
+           torch.empty(B, device="cuda")]
+    ws = torch.empty(gpu.egtp_workspace_bytes(ctx, T, B), dtype=torch.uint8, device="cuda")
+    with pytest.raises(gpu.EgtpError) as e:                       # nothing to read the LM head from yet
+        gpu.egtp_score(ctx, td(w.hidden), off, None, B, T, ws, *out)
+    assert e.value.status == 1
+    with pytest.raises(gpu.EgtpError) as e:                       # and nothing to pack from
+        gpu.egtp_pack_w_lm(ctx, torch.empty_like(packed))
+    assert e.value.status == 1
+    gpu.egtp_adopt_packed_w_lm(ctx, packed)
+    del w_lm_dev
+    ws = torch.empty(gpu.egtp_workspace_bytes(ctx, T, B), dtype=torch.uint8, device="cuda")
+    gpu.egtp_score(ctx, td(w.hidden), off, None, B, T, ws, *out)
+    for k, t in zip(("entropy", "pooled", "lse", "pred"), out):
+        assert np.array_equal(t.cpu().numpy(), ref[k]), k
+    gpu.egtp_destroy(ctx)
+    a.close()
+
+
+def test_malformed_device_offsets_stay_inside_the_buffers(gpu):
+    """Device-side offsets are the caller's word (no host mirror given): whatever they hold, the pooling kernels
+    clamp every token index to [0, T] -- the numbers are then meaningless, the accesses are not wild."""
+    import torch
+    w = _small_bf16(seed=163, B=4, d=64, V=300, d_h=8, lengths=(40, 200, 3, 57))
+    sc = _scorer(gpu, w)
+    hd = gpu.to_device(w.hidden)
+    T, B = w.T, 4
+    for bad in ([0, 40, 240, 243, T + 5000], [0, 500, 100, 243, T], [0, -7, 240, 243, T]):
+        off = torch.tensor(bad, dtype=torch.int32).cuda()
+        out = sc.score(hd, off)
+        pooled, _ = sc.pool_ablation(hd, off, gpu.EGTP_POOL_AVERAGE)
+        last, _ = sc.pool_ablation(hd, off, gpu.EGTP_POOL_LAST)
+        torch.cuda.synchronize()
+        assert out["pooled"].shape == (B, 64) and pooled.shape == (B, 64) and last.shape == (B, 64)
+    good = _np(sc.score(hd, _offsets_on_gpu(gpu, sc, w.lengths)))        # the context is still fine afterwards
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(good, want)
+    sc.close()
+
+
 @pytest.mark.parametrize("B", [1, 63, 64, 65, 130])
 def test_head_batch_tile_boundaries(gpu, B):
     # the first head layer works on 64-sequence tiles and slices d into more pieces the fewer tiles
@@ -215,6 +356,24 @@ def test_many_token_blocks_few_vocabulary_tiles(gpu):
     # cope with a last group that is not full and with fewer vocabulary ranges than asked for
     w = _small_bf16(seed=59, B=4, d=64, V=600, d_h=8, lengths=(700, 1100, 1, 900))
     assert (w.T + 255) // 256 == 11
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(got, want)
+
+
+@pytest.mark.parametrize("d,B,len_mu,n_points", [(96, 24, 6.7, 1), (32, 40, 6.72, 2)])
+def test_paced_multi_tile_sweep_every_token(gpu, d, B, len_mu, n_points):
+    """The launch configuration the serving benchmark runs -- several vocabulary tiles per workgroup (running
+    maximum rescaled from tile to tile, the first half step of a tile issued behind the fold of the previous
+    one) with the cohort pacing switched on -- at a shape the oracle sweeps in full: a small hidden size
+    against many tokens and a large vocabulary.  Every token's entropy, every pooled vector and prediction."""
+    V = 128037                                         # 501 tiles, the last one ragged
+    w = wl.make(wl.scaled(wl.SPECS["mid"], seed=77 + d, B=B, d=d, V=V, d_h=48, len_mu=len_mu, len_sigma=0.7,
+                          len_lo=16, len_hi=4000))
+    plan = gpu.egtp_launch_plan_query(gpu.EGTP_BF16, d, V, w.T)
+    assert plan.paced == 1 and plan.tiles_per_range > 4 * n_points, (w.T, plan.tiles_per_range)
+    assert plan.vocab_tiles % plan.tiles_per_range != 0          # the last range is shorter and leaves early
+    assert w.T % 256 != 0 and plan.token_blocks % 8 != 0           # ragged last block, ragged last group of blocks
     got = _run(gpu, w)
     want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
     assert_egtp_close(got, want)
