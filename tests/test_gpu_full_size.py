@@ -59,12 +59,14 @@ def _block_edge_tokens(T):
 
 
 def _check_gaussian_logit_statistic(w, entropy):
-    """Every token against the closed form of this input recipe.  The logits of a token are (nearly) independent
-    Gaussians of variance s2 = |h|^2 / d, for which H = ln V - s2 / 2 up to the sampling noise of a V-term sum
-    of log-normals: simulated at V = 151936 its standard deviation is 0.003 nat at s2 = 1, 0.012 at s2 = 2,
-    0.06 with heavy tails at s2 = 4 (V = 32000: about twice that).  So the tight bar (0.1 nat) is applied where
-    s2 <= 2, a gross one (1 nat) everywhere, and the mean gap of every 256-token block has to stay below 0.03
-    (a vocabulary range that went missing for a block shifts all its tokens by ln(17/18) = -0.057)."""
+    """Every token against the closed form of this input recipe.  The logits of a token are independent Gaussians
+    of variance s2 = |h|^2 / d (W_lm rows are i.i.d. N(0, 1/d)), for which H = ln V - s2 / 2 up to the sampling
+    noise of a V-term sum of log-normals: simulated at V = 151936 its standard deviation is 0.003 nat at s2 = 1,
+    0.012 at s2 = 2 and 0.06 at s2 = 4, with a heavy tail on the LOW side only -- one logit six standard deviations
+    out takes a tenth of the probability mass and a nat off the entropy (the worst token of the serving batch has
+    such a logit: oracle 8.976 against 10.191 from the formula).  Hence: within 0.1 nat where s2 <= 2, nowhere
+    more than 0.5 above or 2 below, and the mean gap of every 256-token block within 0.03 (a vocabulary range
+    that went missing for a block would shift all its tokens by ln(17/18) = -0.057)."""
     lnV = math.log(w.spec.V)
     s2 = np.empty(w.T)
     for t0 in range(0, w.T, 8192):
@@ -73,13 +75,17 @@ def _check_gaussian_logit_statistic(w, entropy):
         s2[t0:t0 + 8192] = np.einsum("ij,ij->i", h, h, dtype=np.float64) / w.spec.d
     gap = entropy.astype(np.float64) - (lnV - s2 / 2.0)
     calm = s2 <= 2.0
+    nb = w.T // 256
+    block_mean = gap[:nb * 256].reshape(nb, 256).mean(axis=1)
+    seen = (f"calm tokens {int(calm.sum())}: max |gap| {np.abs(gap[calm]).max():.4f}; all: gap in "
+            f"[{gap.min():.4f} (token {gap.argmin()}), {gap.max():.4f} (token {gap.argmax()})]; "
+            f"block mean max |gap| {np.abs(block_mean).max():.4f} (block {np.abs(block_mean).argmax()})")
+    print("[gaussian-logit statistic]", seen)
     assert calm.sum() > w.T // 3
-    assert np.abs(gap[calm]).max() <= 0.1, f"gap {np.abs(gap[calm]).max()} at token {np.nonzero(calm)[0][np.abs(gap[calm]).argmax()]}"
-    assert np.abs(gap).max() <= 1.0, f"gap {np.abs(gap).max()} at token {np.abs(gap).argmax()}"
+    assert np.abs(gap[calm]).max() <= 0.1, seen
+    assert gap.max() <= 0.5 and gap.min() >= -2.0, seen
     if w.spec.V >= 100000:
-        nb = w.T // 256
-        block_mean = gap[:nb * 256].reshape(nb, 256).mean(axis=1)
-        assert np.abs(block_mean).max() <= 0.03, f"block {np.abs(block_mean).argmax()} mean gap {np.abs(block_mean).max()}"
+        assert np.abs(block_mean).max() <= 0.03, seen
 
 
 def _check_sampled(w, off, out, n_seq_sampled, n_short):

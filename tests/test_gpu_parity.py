@@ -298,7 +298,8 @@ def test_context_on_a_packed_lm_head_alone(gpu):
     packed = a._w_packed
     cfg = gpu.egtp_config()
     cfg.vocab, cfg.d, cfg.dtype, cfg.w_lm, cfg.alpha = w.spec.V, w.spec.d, gpu.EGTP_BF16, None, 1.0
-    cfg.head_len = gpu.make_head(td(w.w1), td(w.w2))
+    head_mem = (td(w.w1), td(w.w2))                               # the struct only borrows device memory
+    cfg.head_len = gpu.make_head(*head_mem)
     ctx = gpu.egtp_create(cfg)
     B, T, d = w.spec.B, w.T, w.spec.d
     out = [torch.empty(T, device="cuda"), torch.empty(B, d, device="cuda"), torch.empty(B, device="cuda"),
