@@ -176,6 +176,28 @@ egtp_status plp_step_dist(egtp_ctx *ctx, const void *hidden_new, const int32_t *
                           size_t workspace_bytes, float *entropy_out, float *rem_pred_out,
                           float *p_hat_out, void *stream);
 
+/* plp_step for callers that cannot allocate device memory and have no workspace to bring: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same kernels
+ * as plp_step, run on a scratch array that is part of the library itself: EGTP_STATIC_SCRATCH_BYTES
+ * of device memory, present on every device the library is loaded on until the process ends.  The
+ * call allocates and frees nothing.
+ *   - Limit: egtp_workspace_bytes(ctx, T_new, B) must not exceed egtp_static_scratch_bytes()
+ *     (64 MiB: enough for 512 sequences x 1 token at d = 5120, vocab = 151936, d_h = 1280 with a
+ *     packed W_lm registered -- without one the per-call packed copy alone is over the limit);
+ *     otherwise EGTP_ERR_WORKSPACE and nothing is launched.  Larger batches are the caller's to split.
+ *   - The current device must be the context's (EGTP_ERR_ARCH otherwise).
+ *   - Every call on a device uses that device's one array, whatever the context or stream: calls
+ *     that may overlap in time on one device race.  Order them on one stream or with events.  The
+ *     array keeps the last call's contents; every call rewrites what it reads, so no clearing is
+ *     needed between calls.
+ * Arguments, results and errors are otherwise those of plp_step. */
+#define EGTP_STATIC_SCRATCH_BYTES (64u << 20)
+size_t egtp_static_scratch_bytes(void);
+egtp_status plp_step_static(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                            const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B,
+                            int64_t T_new, float *pooled_state, float *lse_state, float *entropy_out,
+                            float *rem_pred_out, void *stream);
+
 /* Average / max / last-token pooling over the same ragged layout (Table 3's alternatives),
  * followed by head_len.  pooled_out [B x d] fp32, pred_out [B] fp32 (optional).  An empty
  * sequence pools to zeros. */

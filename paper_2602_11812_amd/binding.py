@@ -25,7 +25,7 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
            "egtp_profile_enable", "egtp_profile_read", "egtp_mfma_probe_sink_floats", "egtp_mfma_probe",
-           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm", "egtp_adopt_packed_w_lm", "egtp_score_dist", "plp_step_dist", "egtp_launch_plan_query",
+           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm", "egtp_adopt_packed_w_lm", "egtp_score_dist", "plp_step_dist", "egtp_launch_plan_query", "plp_step_static", "egtp_static_scratch_bytes",
            "egtp_head_train_workspace_bytes", "egtp_head_train_step", "egtp_sjf_order", "egtp_simulate_batches")
 
 
@@ -104,6 +104,10 @@ def load_library() -> ctypes.CDLL:
     lib.plp_step_dist.restype = c_int
     lib.egtp_adopt_packed_w_lm.argtypes = [vp, vp, c_size_t]
     lib.egtp_adopt_packed_w_lm.restype = c_int
+    lib.plp_step_static.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp]
+    lib.plp_step_static.restype = c_int
+    lib.egtp_static_scratch_bytes.argtypes = []
+    lib.egtp_static_scratch_bytes.restype = c_size_t
     lib.egtp_launch_plan_query.argtypes = [c_int, i32, i32, i64, POINTER(egtp_launch_plan)]
     lib.egtp_launch_plan_query.restype = c_int
     lib.egtp_pool_ablation.argtypes = [vp, vp, vp, vp, i32, i64, c_int, vp, c_size_t, vp, vp, vp]
@@ -273,6 +277,20 @@ def plp_step_dist(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, 
                                       _stream(stream))
     if st != EGTP_OK:
         raise EgtpError(st, "plp_step_dist")
+
+
+def egtp_static_scratch_bytes() -> int:
+    return int(load_library().egtp_static_scratch_bytes())
+
+
+def plp_step_static(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state, lse_state,
+                    entropy_out, rem_pred_out, stream=None) -> None:
+    oh = _host_i32(offsets_new_host)
+    st = load_library().plp_step_static(ctx, _dev(hidden_new), _dev(offsets_new_dev), _host_ptr(oh), _dev(slot_dev),
+                                        int(B), int(T_new), _dev(pooled_state), _dev(lse_state), _dev(entropy_out),
+                                        _dev(rem_pred_out), _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "plp_step_static")
 
 
 def plp_step(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state, lse_state,

@@ -19,9 +19,16 @@ struct egtp_ctx {
     int prof_count;
     // packed copy of W_lm for the bf16 matrix-core kernel (caller's memory), or NULL
     const void *w_packed;
+    // this device's copy of the library's static scratch array (plp_step_static)
+    void *static_scratch;
 };
 
 using namespace egtp;
+
+// Scratch of plp_step_static: device memory that exists on every device the library is loaded on,
+// from then until the process ends.  In host code this name only stands for the symbol; the
+// address a kernel can use is looked up, for the device of each context, in egtp_create.
+static __device__ __align__(256) unsigned char scratch[EGTP_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -255,6 +262,13 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
     ctx->prof_cap = 0;
     ctx->prof_count = 0;
     ctx->w_packed = nullptr;
+    ctx->static_scratch = nullptr;
+    // this device's address of the static scratch array (the device is current here)
+    e = hipGetSymbolAddress(&ctx->static_scratch, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ctx->static_scratch) {
+        delete ctx;
+        return EGTP_ERR_HIP;
+    }
     *out = ctx;
     return EGTP_OK;
 }
@@ -423,6 +437,8 @@ egtp_status egtp_adopt_packed_w_lm(egtp_ctx *ctx, const void *packed_dev, size_t
     return EGTP_OK;
 }
 
+size_t egtp_static_scratch_bytes(void) { return (size_t)EGTP_STATIC_SCRATCH_BYTES; }
+
 egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_t B, int32_t *offsets_dev,
                                int32_t *seg_ids_dev, int64_t T, void *stream)
 {
@@ -584,6 +600,27 @@ egtp_status plp_step_dist(egtp_ctx *ctx, const void *hidden_new, const int32_t *
 {
     return step_impl(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state,
                      lse_state, workspace, workspace_bytes, entropy_out, rem_pred_out, p_hat_out, true, stream);
+}
+
+egtp_status plp_step_static(egtp_ctx *ctx, const void *hidden_new, const int32_t *offsets_new_dev,
+                            const int32_t *offsets_new_host, const int32_t *slot_dev, int32_t B, int64_t T_new,
+                            float *pooled_state, float *lse_state, float *entropy_out, float *rem_pred_out,
+                            void *stream)
+{
+    if (!ctx)
+        return EGTP_ERR_NULL;
+    if (B < 0 || T_new < 0 || T_new > 0x7fffffffLL)
+        return EGTP_ERR_SHAPE;
+    // the scratch array is this call's whole workspace: larger batches are the caller's to split
+    const size_t need = egtp_workspace_bytes(ctx, T_new, B);
+    if (need > (size_t)EGTP_STATIC_SCRATCH_BYTES)
+        return EGTP_ERR_WORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return EGTP_ERR_ARCH;  // the array's address was looked up for the context's device
+    return step_impl(ctx, hidden_new, offsets_new_dev, offsets_new_host, slot_dev, B, T_new, pooled_state,
+                     lse_state, ctx->static_scratch, (size_t)EGTP_STATIC_SCRATCH_BYTES, entropy_out,
+                     rem_pred_out, nullptr, false, stream);
 }
 
 egtp_status egtp_pool_ablation(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,
