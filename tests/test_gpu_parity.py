@@ -176,6 +176,19 @@ def test_k_bin_head_expected_value(gpu):
     assert_egtp_close(got, want)
 
 
+def test_positive_scalar_head_to_the_strict_relative_bar(gpu):
+    # a scalar head with a large positive output bias: every prediction is far from zero, so the stated bar
+    # (1e-2 relative) applies as it stands
+    w = _small_bf16(seed=167, B=9, d=192, V=700, d_h=40)
+    b2 = np.array([250.0], dtype=np.float32)
+    b1 = (0.1 * np.random.default_rng(4).normal(size=40)).astype(np.float32)
+    got = _run(gpu, w, b1=b1, b2=b2)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2, b1, b2))
+    assert np.abs(want.pred).min() > 100.0
+    assert_egtp_close(got, want)
+    assert_pred_close(got["pred"], want.pred, strict=True)
+
+
 def test_head_maximum_sizes(gpu):
     # widest head the interface takes: d_h = 16384 hidden units, K = 1024 bins, biases on both
     # layers; bf16 and fp32 weight storage
@@ -189,7 +202,10 @@ def test_head_maximum_sizes(gpu):
     off = oracle.offsets_from_lengths(w.lengths)
     got = _run(gpu, w, w2=wl.to_bf16_bits(w2f), b1=b1, b2=b2, centers=centers)
     head = oracle.Head(w.w1, wl.to_bf16_bits(w2f), b1, b2, centers.astype(np.float64))
-    assert_egtp_close(got, oracle.egtp(w.hidden, off, w.w_lm, head))
+    want = oracle.egtp(w.hidden, off, w.w_lm, head)
+    assert_egtp_close(got, want)
+    assert want.pred.min() >= 1.0                       # expected values over positive centres: no floor needed
+    assert_pred_close(got["pred"], want.pred, strict=True)
     # fp32 storage of the same head
     td = gpu.to_device
     w1f = wl.bf16_bits_to_f32(w.w1)
