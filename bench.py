@@ -191,6 +191,10 @@ def bench_pool(args, gpu, wl, np, torch) -> int:
         times[name] = (time.perf_counter() - t0) / steps
     dt = times["average"]
     gbps = 2.0 * spec.d * T / dt / 1e9
+    # what a plain streaming read of the same 1.13 GB reaches on this device (after the timed region)
+    sink = torch.empty(gpu.egtp_hbm_read_probe_sink_bytes(), dtype=torch.uint8, device="cuda")
+    reads = gpu.egtp_hbm_read_probe(sc.ctx, hidden, sink, 12)
+    read_gbps = float(reads[4:].mean())
     print(json.dumps({
         "metric": f"tokens pooled/sec (average pooling over ragged offsets, d={spec.d})",
         "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 1),
@@ -201,6 +205,8 @@ def bench_pool(args, gpu, wl, np, torch) -> int:
         "ms_per_step_by_pooler": {k: v * 1e3 for k, v in times.items()},
         "roofline": {"kernel": "pool_partial_kernel (sum mode) + join", "bound": "hbm", "achieved": gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None},
+        "hbm_read_probe": {"what": "plain 16-byte-per-lane streaming read of the same hidden states, mean of the "
+                                   "last 8 of 12 launches", "gbps": read_gbps, "achieved_over_probe": gbps / read_gbps},
         "cpu_baseline": None}), flush=True)
     return 0
 

@@ -291,6 +291,19 @@ egtp_status egtp_mfma_probe(egtp_ctx *ctx, float *sink, size_t sink_floats, int3
                             int32_t random_operands, int32_t launches, double *tflops_out_host,
                             void *stream);
 
+/* Measurement aid: the rate at which this device streams a buffer out of HBM with plain 16-byte
+ * loads and nothing else to do -- the reference the pooling kernels (Eq. 4 reads every hidden state
+ * once more) can be set against beside the published bandwidth.  Launches `launches` (1..64) read
+ * kernels over buf_dev[0 .. bytes) back to back on `stream` and blocks until the last has ended.
+ *   buf_dev        device, 16-byte aligned, >= 1 MiB; only read.  Use a buffer much larger than the
+ *                  caches (256 MiB of last-level cache on this part) or the figure is not HBM's
+ *   sink_dev       device, >= egtp_hbm_read_probe_sink_bytes(), overwritten
+ *   gbps_out_host  host: [launches] achieved GB/s (10^9 bytes per second) of each launch
+ * Creates and destroys its events inside the call; allocates no device memory. */
+size_t egtp_hbm_read_probe_sink_bytes(void);
+egtp_status egtp_hbm_read_probe(egtp_ctx *ctx, const void *buf_dev, size_t bytes, void *sink_dev,
+                                size_t sink_bytes, int32_t launches, double *gbps_out_host, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EGTP_POOL_AVERAGE, EGTP_POOL_MAX, EGTP_POOL_LAST = 0, 1, 2
 EXPORTS = ("egtp_create", "egtp_destroy", "egtp_workspace_bytes", "egtp_status_string",
            "egtp_last_hip_error", "egtp_build_offsets", "egtp_score", "plp_step", "egtp_pool_ablation",
            "egtp_profile_enable", "egtp_profile_read", "egtp_mfma_probe_sink_floats", "egtp_mfma_probe",
-           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm", "egtp_adopt_packed_w_lm", "egtp_score_dist", "plp_step_dist", "egtp_launch_plan_query", "plp_step_static", "egtp_static_scratch_bytes",
+           "egtp_packed_w_lm_bytes", "egtp_pack_w_lm", "egtp_adopt_packed_w_lm", "egtp_score_dist", "plp_step_dist", "egtp_launch_plan_query", "egtp_hbm_read_probe", "egtp_hbm_read_probe_sink_bytes", "plp_step_static", "egtp_static_scratch_bytes",
            "egtp_head_train_workspace_bytes", "egtp_head_train_step", "egtp_sjf_order", "egtp_simulate_batches")
 
 
@@ -108,6 +108,10 @@ def load_library() -> ctypes.CDLL:
     lib.plp_step_static.restype = c_int
     lib.egtp_static_scratch_bytes.argtypes = []
     lib.egtp_static_scratch_bytes.restype = c_size_t
+    lib.egtp_hbm_read_probe_sink_bytes.argtypes = []
+    lib.egtp_hbm_read_probe_sink_bytes.restype = c_size_t
+    lib.egtp_hbm_read_probe.argtypes = [vp, vp, c_size_t, vp, c_size_t, i32, vp, vp]
+    lib.egtp_hbm_read_probe.restype = c_int
     lib.egtp_launch_plan_query.argtypes = [c_int, i32, i32, i64, POINTER(egtp_launch_plan)]
     lib.egtp_launch_plan_query.restype = c_int
     lib.egtp_pool_ablation.argtypes = [vp, vp, vp, vp, i32, i64, c_int, vp, c_size_t, vp, vp, vp]
@@ -343,6 +347,20 @@ def egtp_mfma_probe(ctx, sink: torch.Tensor, iters: int, random_operands: bool, 
                                         int(launches), out.ctypes.data_as(c_void_p), _stream(stream))
     if st != EGTP_OK:
         raise EgtpError(st, "egtp_mfma_probe")
+    return out
+
+
+def egtp_hbm_read_probe_sink_bytes() -> int:
+    return int(load_library().egtp_hbm_read_probe_sink_bytes())
+
+
+def egtp_hbm_read_probe(ctx, buf: torch.Tensor, sink: torch.Tensor, launches: int, stream=None) -> np.ndarray:
+    """GB/s of each of `launches` plain streaming reads of `buf` run back to back (blocks until done)."""
+    out = np.zeros(int(launches), dtype=np.float64)
+    st = load_library().egtp_hbm_read_probe(ctx, _dev(buf), _nbytes(buf), _dev(sink), _nbytes(sink), int(launches),
+                                            out.ctypes.data_as(c_void_p), _stream(stream))
+    if st != EGTP_OK:
+        raise EgtpError(st, "egtp_hbm_read_probe")
     return out
 
 

@@ -390,6 +390,42 @@ egtp_status egtp_launch_plan_query(egtp_dtype dtype, int32_t d, int32_t vocab, i
     return EGTP_OK;
 }
 
+size_t egtp_hbm_read_probe_sink_bytes(void) { return (size_t)HBM_PROBE_WORKGROUPS * 256 * sizeof(unsigned); }
+
+egtp_status egtp_hbm_read_probe(egtp_ctx *ctx, const void *buf_dev, size_t bytes, void *sink_dev, size_t sink_bytes,
+                                int32_t launches, double *gbps_out_host, void *stream)
+{
+    if (!ctx || !buf_dev || !sink_dev || !gbps_out_host)
+        return EGTP_ERR_NULL;
+    if (launches < 1 || launches > 64 || bytes < ((size_t)1 << 20) || ((uintptr_t)buf_dev % 16) != 0)
+        return EGTP_ERR_SHAPE;
+    if (sink_bytes < egtp_hbm_read_probe_sink_bytes() || ((uintptr_t)sink_dev % 4) != 0)
+        return EGTP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t ev[65] = {};
+    hipError_t e = hipSuccess;
+    for (int i = 0; i <= launches && e == hipSuccess; ++i)
+        e = hipEventCreate(&ev[i]);
+    if (e == hipSuccess)
+        e = hipEventRecord(ev[0], st);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) {
+        e = hbm_read_probe_launch(buf_dev, bytes, (unsigned *)sink_dev, st);
+        if (e == hipSuccess)
+            e = hipEventRecord(ev[i + 1], st);
+    }
+    if (e == hipSuccess)
+        e = hipEventSynchronize(ev[launches]);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+        gbps_out_host[i] = ms > 0.f ? (double)(bytes / 16 * 16) / ((double)ms * 1e-3) / 1e9 : 0.0;
+    }
+    for (int i = 0; i <= launches; ++i)
+        if (ev[i])
+            (void)hipEventDestroy(ev[i]);
+    return e == hipSuccess ? EGTP_OK : hip_fail(ctx, e);
+}
+
 size_t egtp_workspace_bytes(const egtp_ctx *ctx, int64_t max_tokens, int32_t max_seqs)
 {
     if (!ctx || max_tokens < 0 || max_seqs < 0 || max_tokens > 0x7fffffffLL)

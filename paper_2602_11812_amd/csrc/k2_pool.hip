@@ -7,6 +7,7 @@
 // partial weighted sum (already normalised with the sequence's final log-sum-exp), and a
 // finalize kernel adds a sequence's partials in unit order.  No atomics: bit-reproducible.
 #include "kernels.h"
+#include "stream_load.h"
 #include "wave_reduce.h"
 
 namespace egtp {
@@ -143,8 +144,8 @@ __global__ __launch_bounds__(256) void pool_lse_kernel(const float *__restrict__
 // length when the units are joined); MODE 2: element-wise maxima.
 enum : int { POOL_WEIGHTED = 0, POOL_SUM = 1, POOL_MAXIMUM = 2 };
 
-template <bool BF16>
-__device__ __forceinline__ void widen16(const uint4 &q, float (&h)[BF16 ? 8 : 4])
+template <bool BF16, typename Q>
+__device__ __forceinline__ void widen16(const Q &q, float (&h)[BF16 ? 8 : 4])
 {
     if (BF16) {
         const unsigned v[4] = {q.x, q.y, q.z, q.w};
@@ -165,10 +166,14 @@ template <bool BF16, int MODE>
 __global__ __launch_bounds__(256) void pool_partial_kernel(
     const void *__restrict__ hidden, int d, const float *__restrict__ entropy,
     const int32_t *__restrict__ offsets, int32_t B, long T, float inv_alpha, const float *__restrict__ lse_new,
-    const int32_t *__restrict__ unit_start, float *__restrict__ partial)
+    const int32_t *__restrict__ unit_start, int ysplit, float *__restrict__ partial)
 {
     __shared__ float w[POOL_UNIT];
-    const int u = blockIdx.x;  // the grid is pool_units_bound(T, B): u indexes inside the partial buffer
+    // Workgroup = (unit, feature slice), the slice varying fastest so that the slices of a unit -- pieces of
+    // the same token rows -- are read at about the same time.  The grid holds pool_units_bound(T, B) units:
+    // u indexes inside the partial buffer.
+    const int u = blockIdx.x / ysplit;
+    const int yslice = blockIdx.x - u * ysplit;
     if (u >= unit_start[B])
         return;
     const int b = find_segment(unit_start, B, u);
@@ -183,14 +188,16 @@ __global__ __launch_bounds__(256) void pool_partial_kernel(
     constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte load
     const int nchunk = d / VEC;
     float *out = partial + (long)u * d;
-    for (int c = threadIdx.x; c < nchunk; c += 256) {
+    // a slice is 256 chunks of 16 bytes, one per thread (two slices at d = 4096: twice as many workgroups as
+    // units, which evens out the end of the launch)
+    for (int c = yslice * 256 + threadIdx.x; c < nchunk; c += 256 * ysplit) {
         float acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
             acc[e] = MODE == POOL_MAXIMUM ? NEG_INF : 0.f;
         const unsigned char *p = (const unsigned char *)hidden + (t0 * d + (long)c * VEC) * (BF16 ? 2 : 4);
         const long stride = (long)d * (BF16 ? 2 : 4);
-        auto fold = [&](const uint4 &q, int i) {
+        auto fold = [&](const u32x4 &q, int i) {
             float h[VEC];
             widen16<BF16>(q, h);
             const float wi = MODE == POOL_WEIGHTED ? w[i] : 1.f;
@@ -202,23 +209,56 @@ __global__ __launch_bounds__(256) void pool_partial_kernel(
         };
         int i = 0;
         for (; i + 8 <= n; i += 8) {  // eight rows in flight per thread
-            uint4 q[8];
+            u32x4 q[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r)
-                q[r] = *(const uint4 *)(p + (long)(i + r) * stride);
+                q[r] = stream_load16(p + (long)(i + r) * stride);
 #pragma unroll
             for (int r = 0; r < 8; ++r)
                 fold(q[r], i + r);
         }
         for (; i < n; ++i)
-            fold(*(const uint4 *)(p + (long)i * stride), i);
+            fold(stream_load16(p + (long)i * stride), i);
 #pragma unroll
         for (int e = 0; e < VEC; e += 4)
             *(float4 *)(out + (long)c * VEC + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
     }
 }
 
-// ---- Table 3 alternatives: join a sequence's unit partials (sum / length, or maximum) -------
+// ---- joining a sequence's unit partials ----------------------------------------------------------
+// Thread = four consecutive features of one sequence; the partials are combined in unit order (a fixed
+// order: bit-reproducible), JOIN_AHEAD of them fetched before any is used -- a sequence of 8192 tokens
+// has 64 units, and one load at a time would make the join a chain of 64 memory latencies.
+constexpr int JOIN_AHEAD = 8;
+
+template <int MODE>
+__device__ __forceinline__ float4 join_units(const float *__restrict__ partial, int u0, int u1, int d, int k,
+                                             float init)
+{
+    float4 r = make_float4(init, init, init, init);
+    auto add = [&](const float4 &v) {
+        if (MODE == POOL_MAXIMUM) {
+            r.x = fmaxf(r.x, v.x), r.y = fmaxf(r.y, v.y), r.z = fmaxf(r.z, v.z), r.w = fmaxf(r.w, v.w);
+        } else {
+            r.x += v.x, r.y += v.y, r.z += v.z, r.w += v.w;
+        }
+    };
+    int u = u0;
+    for (; u + JOIN_AHEAD <= u1; u += JOIN_AHEAD) {
+        float4 v[JOIN_AHEAD];
+#pragma unroll
+        for (int i = 0; i < JOIN_AHEAD; ++i)
+            v[i] = *(const float4 *)(partial + (long)(u + i) * d + k);
+#pragma unroll
+        for (int i = 0; i < JOIN_AHEAD; ++i)
+            add(v[i]);
+    }
+    for (; u < u1; ++u)
+        add(*(const float4 *)(partial + (long)u * d + k));
+    return r;
+}
+
+// Table 3 alternatives: sum / length, or maximum
 template <int MODE>
 __global__ __launch_bounds__(256) void pool_finalize_plain_kernel(const float *__restrict__ partial,
                                                                   const int32_t *__restrict__ unit_start,
@@ -226,22 +266,21 @@ __global__ __launch_bounds__(256) void pool_finalize_plain_kernel(const float *_
                                                                   int units_cap, float *__restrict__ out_pooled)
 {
     const int b = blockIdx.x;
-    const int k = blockIdx.y * 256 + threadIdx.x;
+    const int k = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (k >= d)
         return;
     const int u0 = unit_start[b], u1 = min(unit_start[b + 1], units_cap);
     const int len = offsets[b + 1] - offsets[b];
-    float r = (MODE == POOL_MAXIMUM && len > 0) ? NEG_INF : 0.f;  // an empty sequence pools to zero
-    for (int u = u0; u < u1; ++u) {
-        const float v = partial[(long)u * d + k];
-        r = MODE == POOL_MAXIMUM ? fmaxf(r, v) : r + v;
+    // an empty sequence pools to zero
+    float4 r = join_units<MODE>(partial, u0, u1, d, k, (MODE == POOL_MAXIMUM && len > 0) ? NEG_INF : 0.f);
+    if (MODE == POOL_SUM && len > 0) {
+        const float inv = 1.0f / (float)len;
+        r.x *= inv, r.y *= inv, r.z *= inv, r.w *= inv;
     }
-    if (MODE == POOL_SUM && len > 0)
-        r *= 1.0f / (float)len;
-    out_pooled[(long)b * d + k] = r;
+    *(float4 *)(out_pooled + (long)b * d + k) = r;
 }
 
-// ---- sum a sequence's partials in unit order, add the rescaled old state ------------------
+// Eq. 4 / Eq. 8: the sum of a sequence's partials plus the rescaled old state
 __global__ __launch_bounds__(256) void pool_finalize_kernel(
     const float *__restrict__ partial, const int32_t *__restrict__ unit_start,
     const int32_t *__restrict__ slot, int d, int units_cap, const float *state_pooled,
@@ -249,17 +288,18 @@ __global__ __launch_bounds__(256) void pool_finalize_kernel(
     float *out_lse)
 {
     const int b = blockIdx.x;
-    const int k = blockIdx.y * 256 + threadIdx.x;
+    const int k = (blockIdx.y * 256 + threadIdx.x) * 4;
     const int s = slot ? slot[b] : b;
     if (k < d) {
         const int u0 = unit_start[b], u1 = min(unit_start[b + 1], units_cap);
-        float sum = 0.f;
-        for (int u = u0; u < u1; ++u)
-            sum += partial[(long)u * d + k];
+        float4 sum = join_units<POOL_SUM>(partial, u0, u1, d, k, 0.f);
         const float sc = state_scale[b];
-        if (state_pooled && sc != 0.f)
-            sum = fmaf(state_pooled[(long)s * d + k], sc, sum);
-        out_pooled[(long)s * d + k] = sum;
+        if (state_pooled && sc != 0.f) {
+            const float4 old = *(const float4 *)(state_pooled + (long)s * d + k);
+            sum.x = fmaf(old.x, sc, sum.x), sum.y = fmaf(old.y, sc, sum.y);
+            sum.z = fmaf(old.z, sc, sum.z), sum.w = fmaf(old.w, sc, sum.w);
+        }
+        *(float4 *)(out_pooled + (long)s * d + k) = sum;
     }
     if (blockIdx.y == 0 && threadIdx.x == 0)
         out_lse[s] = lse_new[b];
@@ -346,6 +386,14 @@ __global__ __launch_bounds__(256) void pool_last_kernel(const void *__restrict__
 
 }  // namespace
 
+// workgroups a unit's features are spread over: one 16-byte chunk per thread
+static unsigned pool_feature_split(int d, bool bf16)
+{
+    const int nchunk = d / (bf16 ? 8 : 4);
+    const int n = (nchunk + 255) / 256;
+    return (unsigned)(n < 1 ? 1 : (n > 64 ? 64 : n));
+}
+
 hipError_t scan_lengths(const int32_t *lengths, int32_t B, int32_t *offsets, hipStream_t st)
 {
     hipLaunchKernelGGL(scan_kernel<false>, dim3(1), dim3(256), 0, st, lengths, B, offsets);
@@ -381,13 +429,16 @@ hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
     const long units = pool_units_bound(a.T, a.B);
     if (units > 0x7fffffffL)
         return hipErrorInvalidValue;
+    const unsigned ysplit = pool_feature_split(a.d, bf16);
+    if (units * ysplit > 0x7fffffffL)
+        return hipErrorInvalidValue;
     if (bf16)
-        hipLaunchKernelGGL((pool_partial_kernel<true, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
-                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
+        hipLaunchKernelGGL((pool_partial_kernel<true, POOL_WEIGHTED>), dim3((unsigned)(units * ysplit)), dim3(256), 0, st, a.hidden,
+                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, (int)ysplit, a.partial);
     else
-        hipLaunchKernelGGL((pool_partial_kernel<false, POOL_WEIGHTED>), dim3((unsigned)units), dim3(256), 0, st, a.hidden,
-                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, a.partial);
-    hipLaunchKernelGGL(pool_finalize_kernel, dim3(a.B, (a.d + 255) / 256), dim3(256), 0, st, a.partial,
+        hipLaunchKernelGGL((pool_partial_kernel<false, POOL_WEIGHTED>), dim3((unsigned)(units * ysplit)), dim3(256), 0, st, a.hidden,
+                           a.d, a.entropy, a.offsets, a.B, (long)a.T, a.inv_alpha, a.lse_new, a.unit_start, (int)ysplit, a.partial);
+    hipLaunchKernelGGL(pool_finalize_kernel, dim3(a.B, (a.d + 1023) / 1024), dim3(256), 0, st, a.partial,
                        a.unit_start, a.slot, a.d, (int)units, a.state_pooled, a.state_scale, a.lse_new, a.out_pooled,
                        a.out_lse);
     return hipGetLastError();
@@ -414,12 +465,15 @@ hipError_t pool_plain(const void *hidden, int dtype, int d, const int32_t *offse
     const long units = pool_units_bound(T, B);
     if (units > 0x7fffffffL)
         return hipErrorInvalidValue;
+    const unsigned ysplit = pool_feature_split(d, bf16);
+    if (units * ysplit > 0x7fffffffL)
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(256), 0, st, offsets, B, unit_start);
-    const dim3 fgrid(B, (d + 255) / 256);
+    const dim3 fgrid(B, (d + 1023) / 1024);
 #define EGTP_POOL_PLAIN(BF, MODE)                                                                          \
     do {                                                                                                   \
-        hipLaunchKernelGGL((pool_partial_kernel<BF, MODE>), dim3((unsigned)units), dim3(256), 0, st, hidden, \
-                           d, nullptr, offsets, B, (long)T, 0.f, nullptr, unit_start, partial);            \
+        hipLaunchKernelGGL((pool_partial_kernel<BF, MODE>), dim3((unsigned)(units * ysplit)), dim3(256), 0, st, hidden, \
+                           d, nullptr, offsets, B, (long)T, 0.f, nullptr, unit_start, (int)ysplit, partial); \
         hipLaunchKernelGGL(pool_finalize_plain_kernel<MODE>, fgrid, dim3(256), 0, st, partial, unit_start, \
                            offsets, d, (int)units, out_pooled);                                            \
     } while (0)

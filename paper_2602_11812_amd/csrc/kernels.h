@@ -150,4 +150,10 @@ constexpr int MFMA_PROBE_WORKGROUPS = 1024;
 double mfma_probe_flop(int iters);
 hipError_t mfma_probe_launch(float *sink, int iters, int random_operands, hipStream_t st);
 
+
+// Plain streaming read of a buffer (measurement aid): HBM_PROBE_WORKGROUPS workgroups, each reading one
+// contiguous slab with 16-byte loads; sink holds one word per thread.
+constexpr int HBM_PROBE_WORKGROUPS = 8192;
+hipError_t hbm_read_probe_launch(const void *buf, size_t bytes, unsigned *sink, hipStream_t st);
+
 }  // namespace egtp
