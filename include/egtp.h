@@ -256,7 +256,7 @@ egtp_status egtp_head_train_step(const egtp_head_train *head, const float *x, co
  * one workgroup per (block of tokens_per_block tokens, range of tiles_per_range vocabulary tiles of
  * rows_per_tile rows); each leaves one partial (max, sum, weighted sum) triple per token, merged
  * afterwards.  paced = 1 when the bf16 kernel's workgroups keep each other in step (ranges longer
- * than four tiles).  Pure host arithmetic: no device, no context.  Tests use it to make sure
+ * than four tiles, at least eight token blocks).  Pure host arithmetic: no device, no context.  Tests use it to make sure
  * that a shape reaches the launch configuration they mean to cover. */
 typedef struct {
     int32_t tokens_per_block, rows_per_tile;

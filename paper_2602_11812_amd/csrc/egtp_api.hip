@@ -129,9 +129,10 @@ egtp_status hip_fail(egtp_ctx *ctx, hipError_t e)
             return hip_fail(ctx, e_); \
     } while (0)
 
-// Eq. 2 for T tokens: fused partials, then the per-token merge into `entropy`.
+// Eq. 2 for T tokens: fused partials, then the per-token merge into `entropy` -- unless the caller merges
+// them itself (nsplit_left != NULL receives the number of ranges still to be merged).
 egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Workspace &w, float *entropy,
-                        hipStream_t st)
+                        hipStream_t st, int *nsplit_left = nullptr)
 {
     const egtp_config &c = ctx->cfg;
     const K1Plan p = k1_plan(c.dtype, T, c.d, c.vocab);
@@ -155,7 +156,10 @@ egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Work
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count + 1], st));
         ++ctx->prof_count;
     }
-    EGTP_HIP(k1_merge(w.k1_part, p.nsplit, T, entropy, st));
+    if (nsplit_left)
+        *nsplit_left = p.nsplit;
+    else
+        EGTP_HIP(k1_merge(w.k1_part, p.nsplit, T, entropy, st));
     return EGTP_OK;
 }
 
@@ -527,6 +531,8 @@ egtp_status score_impl(egtp_ctx *ctx, const void *hidden, const int32_t *offsets
     a.dtype = c.dtype;
     a.d = c.d;
     a.entropy = entropy;
+    a.k1_part = nullptr;
+    a.k1_nsplit = 0;
     a.offsets = offsets_dev;
     a.slot = nullptr;
     a.B = B;
@@ -573,7 +579,10 @@ egtp_status step_impl(egtp_ctx *ctx, const void *hidden_new, const int32_t *offs
     const egtp_config &c = ctx->cfg;
     const Workspace w = carve(ctx, workspace, T_new, B);
     float *entropy = entropy_out ? entropy_out : w.entropy;
-    if (T_new > 0 && (s = run_entropy(ctx, hidden_new, T_new, w, entropy, st)) != EGTP_OK)
+    // one token per sequence: the state update finishes the entropy itself (one launch less per decode step)
+    int nsplit_left = 0;
+    if (T_new > 0 &&
+        (s = run_entropy(ctx, hidden_new, T_new, w, entropy, st, offsets_new_dev ? nullptr : &nsplit_left)) != EGTP_OK)
         return s;
 
     PoolArgs a;
@@ -581,6 +590,8 @@ egtp_status step_impl(egtp_ctx *ctx, const void *hidden_new, const int32_t *offs
     a.dtype = c.dtype;
     a.d = c.d;
     a.entropy = entropy;
+    a.k1_part = nsplit_left > 0 ? w.k1_part : nullptr;
+    a.k1_nsplit = nsplit_left;
     a.offsets = offsets_new_dev;
     a.slot = slot_dev;
     a.B = B;

@@ -12,7 +12,7 @@ static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
 static constexpr int NUM_CUS = 256;
 static constexpr int NSPLIT_SLACK = 8;  // how far above the minimum the number of ranges may go
 
-K1Plan k1_plan(int dtype, int64_t T, int /*d*/, int V)
+K1Plan k1_plan(int dtype, int64_t T, int d, int V)
 {
     K1Plan p;
     const bool bf = dtype == DT_BF16;
@@ -24,12 +24,34 @@ K1Plan k1_plan(int dtype, int64_t T, int /*d*/, int V)
     int ns0 = p.ntb > 0 ? (target + p.ntb - 1) / p.ntb : 1;
     if (ns0 < 1)
         ns0 = 1;
+    p.nsplit = 1;
+    p.tiles_per_split = p.ntiles_v;
+    if (ns0 >= p.ntiles_v) {
+        // A small batch: even one range per vocabulary tile gives fewer workgroups than asked for.  What
+        // counts then is the number of rounds the compute units need and what every workgroup pays to
+        // start and finish (filling the load ring, the final merge and stores: about START_STEPS K steps
+        // of a sweep of 2 ceil(d / 64) steps per tile).  512 tokens against 594 tiles are 1188 single-tile
+        // workgroups = 5 rounds of starts, or 238 workgroups of 5 tiles each = one round of the same length.
+        constexpr double START_STEPS = 6.0;
+        const double start_tiles = START_STEPS / (2.0 * ((d + 63) / 64));
+        double best_cost = 0.0;
+        for (int tps = 1; tps <= p.ntiles_v && tps <= 64; ++tps) {
+            const int nsplit = (p.ntiles_v + tps - 1) / tps;
+            const long units = (long)p.ntb * nsplit;
+            const long rounds = (units + NUM_CUS - 1) / NUM_CUS;
+            const double cost = (double)rounds * ((double)tps + start_tiles);
+            if (tps == 1 || cost < best_cost - 1e-9) {
+                best_cost = cost;
+                p.nsplit = nsplit;
+                p.tiles_per_split = tps;
+            }
+        }
+        return p;
+    }
     // One workgroup per (token block, vocabulary range), one workgroup per compute unit at a
     // time, all of about the same length: among the next few range counts take the one whose
     // last round of workgroups is fullest.
     double best = -1.0;
-    p.nsplit = 1;
-    p.tiles_per_split = p.ntiles_v;
     for (int ns = ns0; ns <= ns0 + NSPLIT_SLACK; ++ns) {
         const int nsc = ns > p.ntiles_v ? p.ntiles_v : ns;
         const int tps = (p.ntiles_v + nsc - 1) / nsc;

@@ -41,6 +41,11 @@ size_t k1_pace_ints_bound(int dtype, int64_t T, int d, int V);
 // A range of the bf16 kernel has a pacing point after every K1_PACE_TILES vocabulary tiles, so only
 // ranges longer than that pace at all.
 constexpr int K1_PACE_TILES = 4;
-inline bool k1_plan_paces(int dtype, const K1Plan &p) { return dtype == DT_BF16 && p.tiles_per_split > K1_PACE_TILES; }
+// Pacing serves the token blocks that share vocabulary tiles in an XCD's L2 (groups of eight): a batch of
+// fewer blocks streams W_lm once from HBM whatever the workgroups' relative progress.
+inline bool k1_plan_paces(int dtype, const K1Plan &p)
+{
+    return dtype == DT_BF16 && p.tiles_per_split > K1_PACE_TILES && p.ntb >= 8;
+}
 
 }  // namespace egtp

@@ -6,7 +6,7 @@
 // POOL_UNIT tokens so that long and short sequences load the chip evenly; each unit leaves a
 // partial weighted sum (already normalised with the sequence's final log-sum-exp), and a
 // finalize kernel adds a sequence's partials in unit order.  No atomics: bit-reproducible.
-#include "kernels.h"
+#include "k1_common.h"
 #include "stream_load.h"
 #include "wave_reduce.h"
 
@@ -306,16 +306,57 @@ __global__ __launch_bounds__(256) void pool_finalize_kernel(
 }
 
 // ---- Eq. 8 fast path: exactly one new token per sequence ------------------------------------
+// With part != NULL the kernel first finishes Eq. 2 for its token -- the nsplit partial (m, S, U) triples the
+// fused kernel left for it are merged by a fixed tree (thread i takes ranges i, i + 256, ... in order, then an
+// xor tree inside each wave, then the four waves in order) -- and writes H to entropy[b]; otherwise entropy[b]
+// is read.
 template <bool BF16>
-__global__ __launch_bounds__(256) void plp_fold1_kernel(const void *__restrict__ hidden, int d,
-                                                        const float *__restrict__ entropy,
+__global__ __launch_bounds__(256) void plp_fold1_kernel(const void *__restrict__ hidden, int d, float *entropy,
+                                                        const float *__restrict__ part, int nsplit, long T,
                                                         const int32_t *__restrict__ slot, float inv_alpha,
                                                         float *pooled_state, float *lse_state)
 {
+    __shared__ float red[4][3];
     const int b = blockIdx.x;
     const int s = slot ? slot[b] : b;
+    float H;
+    if (part != nullptr) {
+        const long plane = (long)nsplit * T;
+        Stats acc;
+        acc.m = NEG_BIG, acc.S = 0.f, acc.U = 0.f;
+        for (int r = threadIdx.x; r < nsplit; r += 256) {
+            const long idx = (long)r * T + b;
+            Stats o;
+            o.m = part[idx], o.S = part[plane + idx], o.U = part[2 * plane + idx];
+            acc = merge(acc, o);
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            Stats o;
+            o.m = __shfl_xor(acc.m, off), o.S = __shfl_xor(acc.S, off), o.U = __shfl_xor(acc.U, off);
+            acc = merge(acc, o);
+        }
+        if ((threadIdx.x & 63) == 0) {
+            red[threadIdx.x >> 6][0] = acc.m;
+            red[threadIdx.x >> 6][1] = acc.S;
+            red[threadIdx.x >> 6][2] = acc.U;
+        }
+        __syncthreads();
+        acc.m = red[0][0], acc.S = red[0][1], acc.U = red[0][2];
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+            Stats o;
+            o.m = red[k][0], o.S = red[k][1], o.U = red[k][2];
+            acc = merge(acc, o);
+        }
+        H = logf(acc.S) - acc.U * 0.6931471805599453f / acc.S;
+        if (threadIdx.x == 0)
+            entropy[b] = H;
+    } else {
+        H = entropy[b];
+    }
     const float L_old = lse_state[s];
-    const float a = entropy[b] * inv_alpha;
+    const float a = H * inv_alpha;
     const float M = fmaxf(L_old, a);
     const float old = L_old > NEG_INF ? __expf(L_old - M) : 0.f;
     const float L = M + __logf(old + __expf(a - M));
@@ -416,11 +457,11 @@ hipError_t pool_entropy_weighted(const PoolArgs &a, hipStream_t st)
     const bool bf16 = a.dtype == DT_BF16;
     if (a.offsets == nullptr) {  // one new token per sequence, folded in place
         if (bf16)
-            hipLaunchKernelGGL(plp_fold1_kernel<true>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d,
-                               a.entropy, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
+            hipLaunchKernelGGL(plp_fold1_kernel<true>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d, a.entropy,
+                               a.k1_part, a.k1_nsplit, (long)a.T, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
         else
-            hipLaunchKernelGGL(plp_fold1_kernel<false>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d,
-                               a.entropy, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
+            hipLaunchKernelGGL(plp_fold1_kernel<false>, dim3(a.B), dim3(256), 0, st, a.hidden, a.d, a.entropy,
+                               a.k1_part, a.k1_nsplit, (long)a.T, a.slot, a.inv_alpha, a.out_pooled, a.out_lse);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(256), 0, st, a.offsets, a.B, a.unit_start);

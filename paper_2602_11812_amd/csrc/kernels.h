@@ -72,7 +72,9 @@ struct PoolArgs {
     const void *hidden;       // [T x d]
     int dtype;
     int d;
-    const float *entropy;     // [T]
+    float *entropy;           // [T]; read, or -- one token per sequence with k1_part set -- written
+    const float *k1_part;     // one token per sequence only: the fused kernel's partial triples, still to be
+    int k1_nsplit;            //   merged into entropy (k1_nsplit ranges), or NULL = entropy is final
     const int32_t *offsets;   // [B+1], or NULL = one token per sequence
     const int32_t *slot;      // [B] or NULL
     int32_t B;

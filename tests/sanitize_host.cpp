@@ -325,8 +325,11 @@ void plan_checks()
     const K1Plan serving = k1_plan(DT_BF16, 137720, 4096, 151936);
     CHECK(serving.tiles_per_split > K1_PACE_TILES && k1_plan_paces(DT_BF16, serving));
     CHECK(!k1_plan_paces(DT_F32, serving));
+    // 512 decode tokens: two token blocks, and one round of workgroups rather than five rounds of single tiles
     const K1Plan decode = k1_plan(DT_BF16, 512, 4096, 151936);
-    CHECK(decode.ntb == 2 && !k1_plan_paces(DT_BF16, decode));
+    CHECK(decode.ntb == 2 && (long)decode.ntb * decode.nsplit <= 256 && decode.tiles_per_split == 5);
+    const K1Plan one_tile = k1_plan(DT_BF16, 10, 64, 200);
+    CHECK(one_tile.nsplit == 1 && one_tile.tiles_per_split == 1 && !k1_plan_paces(DT_BF16, one_tile));
 }
 
 }  // namespace
