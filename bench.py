@@ -390,7 +390,13 @@ def main() -> int:
         "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": traffic if args.workload == "serving" else None,
-                     "avg_launch_ms": k1_avg_s * 1e3, "launches": int(k1_ms.size)},
+                     "traffic_source": ("profiles/k1_entropy_bf16_serving_hbm_traffic.txt (rocprofv3 FETCH_SIZE + "
+                                        "WRITE_SIZE passes of an earlier run of this kernel; replayed while the kernel "
+                                        "and launch-plan sources hash to the recorded value, not measured in this run)")
+                     if traffic is not None and args.workload == "serving" else None,
+                     "frac_of_measured_mfma_rate": (achieved / probe["random_operands_tflops"]) if probe else None,
+                     "avg_launch_ms": k1_avg_s * 1e3, "min_launch_ms": float(k1_ms.min()),
+                     "max_launch_ms": float(k1_ms.max()), "launches": int(k1_ms.size)},
         "mfma_probe": probe,
         "library_gemm": lib_gemm,
         "cpu_baseline": cpu,
