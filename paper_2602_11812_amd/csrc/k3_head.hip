@@ -15,6 +15,7 @@
 // would, in fp32.  Fragments come straight from global memory: a lane's 8 K-elements are 16
 // contiguous bytes of a weight row and 32 contiguous bytes of a pooled row.
 #include "kernels.h"
+#include "partial_planes.h"
 #include "wave_reduce.h"
 
 namespace egtp {
@@ -298,16 +299,28 @@ __global__ __launch_bounds__(256) void head_layer2_kernel(const float *__restric
 {
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    extern __shared__ float a[];
+    extern __shared__ __align__(16) float a[];
     float *partial = a + d_h;
     // hidden activations: partial sums in split order, then bias and ReLU; kept in LDS
-    for (int j = tid; j < d_h; j += 256) {
-        float pre = 0.f;
+    if ((d_h & 3) == 0) {
+        for (int j = tid * 4; j < d_h; j += 1024) {
+            const float4 pre = sum_planes4(act_part, nks, B, b, d_h, j);
+            const float v[4] = {pre.x, pre.y, pre.z, pre.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = v[i] + (b1 ? b1[j + i] : 0.f);
+                a[j + i] = p > 0.f ? p : 0.f;
+            }
+        }
+    } else {
+        for (int j = tid; j < d_h; j += 256) {
+            float pre = 0.f;
 #pragma unroll 8
-        for (int z = 0; z < nks; ++z)
-            pre += act_part[((long)z * B + b) * d_h + j];
-        pre += b1 ? b1[j] : 0.f;
-        a[j] = pre > 0.f ? pre : 0.f;
+            for (int z = 0; z < nks; ++z)
+                pre += act_part[((long)z * B + b) * d_h + j];
+            pre += b1 ? b1[j] : 0.f;
+            a[j] = pre > 0.f ? pre : 0.f;
+        }
     }
     __syncthreads();
     // every wave takes a quarter of each dot product (fixed assignment: bit-reproducible)

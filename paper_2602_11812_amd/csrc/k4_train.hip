@@ -13,9 +13,10 @@
 //                          is never written unless the caller asks for a copy.  With the
 //                          paper's batch of 16 this kernel is a pure stream over W1 and its two
 //                          moments (read and written once each).
-//   5. loss                fixed-order sum of the per-sample terms
+//   5. loss                fixed-order sum of the per-sample terms (one more workgroup of launch 3)
 // No floating-point atomics anywhere: results are bit-reproducible.
 #include "kernels.h"
+#include "partial_planes.h"
 #include "wave_reduce.h"
 
 namespace egtp {
@@ -44,32 +45,59 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
     float lambda, float *__restrict__ act, float *__restrict__ dact, float *__restrict__ dz_out,
     float *__restrict__ loss_part)
 {
-    extern __shared__ float sm[];
+    extern __shared__ __align__(16) float sm[];
     float *a = sm;
     float *z = a + d_h;
     float *dz = z + K;
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    for (int j = tid; j < d_h; j += 256) {
-        float pre = 0.f;
+    // pre-activations: the slices' partial sums, added in slice order
+    if ((d_h & 3) == 0) {
+        for (int j = tid * 4; j < d_h; j += 1024) {
+            const float4 pre = sum_planes4(act_part, nks, B, b, d_h, j);
+            float4 r;  // the caller's bias vector need not be 16-byte aligned
+            r.x = fmaxf(pre.x + b1[j], 0.f), r.y = fmaxf(pre.y + b1[j + 1], 0.f);
+            r.z = fmaxf(pre.z + b1[j + 2], 0.f), r.w = fmaxf(pre.w + b1[j + 3], 0.f);
+            *(float4 *)(a + j) = r;
+            *(float4 *)(act + (long)b * d_h + j) = r;
+        }
+    } else {
+        for (int j = tid; j < d_h; j += 256) {
+            float pre = 0.f;
 #pragma unroll 8
-        for (int s = 0; s < nks; ++s)
-            pre += act_part[((long)s * B + b) * d_h + j];
-        pre += b1[j];
-        const float r = pre > 0.f ? pre : 0.f;
-        a[j] = r;
-        act[(long)b * d_h + j] = r;
+            for (int s = 0; s < nks; ++s)
+                pre += act_part[((long)s * B + b) * d_h + j];
+            pre += b1[j];
+            const float r = pre > 0.f ? pre : 0.f;
+            a[j] = r;
+            act[(long)b * d_h + j] = r;
+        }
     }
     __syncthreads();
-    for (int o = wave; o < K; o += 4) {
-        float s = 0.f;
-#pragma unroll 8
-        for (int j = lane; j < d_h; j += 64)
-            s = fmaf(w2[(long)o * d_h + j], a[j], s);
-        s = wave_sum(s) + b2[o];
-        if (lane == 0)
-            z[o] = s;
+    // logits: a wave takes OUTS_AT_ONCE outputs at a time so that their weight loads are all in flight together
+    // (W2 is small and cache-resident; what costs is the latency of each dependent round of loads)
+    constexpr int OUTS_AT_ONCE = 5;
+    for (int o0 = wave * OUTS_AT_ONCE; o0 < K; o0 += 4 * OUTS_AT_ONCE) {
+        float s[OUTS_AT_ONCE];
+#pragma unroll
+        for (int q = 0; q < OUTS_AT_ONCE; ++q)
+            s[q] = 0.f;
+#pragma unroll 4
+        for (int j = lane; j < d_h; j += 64) {
+            const float aj = a[j];
+#pragma unroll
+            for (int q = 0; q < OUTS_AT_ONCE; ++q) {
+                const int o = o0 + q < K ? o0 + q : K - 1;  // past the end: a valid row, not used
+                s[q] = fmaf(w2[(long)o * d_h + j], aj, s[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < OUTS_AT_ONCE; ++q) {
+            const float t = wave_sum(s[q]);
+            if (lane == 0 && o0 + q < K)
+                z[o0 + q] = t + b2[o0 + q];
+        }
     }
     __syncthreads();
     if (wave == 0) {
@@ -112,12 +140,41 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
         }
     }
     __syncthreads();
+    // d loss / d pre-activation = (W2^T dz) where the unit is active; many rows of W2 in flight per thread
     for (int j = tid; j < d_h; j += 256) {
         float s = 0.f;
-#pragma unroll 4
+#pragma unroll 20
         for (int o = 0; o < K; ++o)
             s = fmaf(dz[o], w2[(long)o * d_h + j], s);
         dact[(long)b * d_h + j] = a[j] > 0.f ? s : 0.f;
+    }
+}
+
+// ---- 5. loss = {lambda CE + (1 - lambda) MSE, CE, MSE}, fixed summation order -----------------
+// (one workgroup of 256 threads; runs as the last workgroup of the small-parameter kernel)
+__device__ void sum_loss(const float *__restrict__ loss_part, int B, float lambda, float *__restrict__ loss)
+{
+    __shared__ float red[2][256];
+    const int tid = threadIdx.x;
+    float ce = 0.f, mse = 0.f;
+    for (int b = tid; b < B; b += 256) {
+        ce += loss_part[2 * b];
+        mse += loss_part[2 * b + 1];
+    }
+    red[0][tid] = ce;
+    red[1][tid] = mse;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) {
+            red[0][tid] += red[0][tid + s];
+            red[1][tid] += red[1][tid + s];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        loss[0] = lambda * red[0][0] + (1.0f - lambda) * red[1][0];
+        loss[1] = red[0][0];
+        loss[2] = red[1][0];
     }
 }
 
@@ -127,8 +184,12 @@ __global__ __launch_bounds__(256) void train_small_update_kernel(
     int K, Adam h, float *__restrict__ w2, float *__restrict__ m_w2, float *__restrict__ v_w2,
     float *__restrict__ b2, float *__restrict__ m_b2, float *__restrict__ v_b2, float *__restrict__ b1,
     float *__restrict__ m_b1, float *__restrict__ v_b1, float *__restrict__ g_w2, float *__restrict__ g_b2,
-    float *__restrict__ g_b1)
+    float *__restrict__ g_b1, const float *__restrict__ loss_part, float lambda, float *__restrict__ loss)
 {
+    if (blockIdx.x == gridDim.x - 1) {  // one extra workgroup: the loss of the batch (5.)
+        sum_loss(loss_part, B, lambda, loss);
+        return;
+    }
     const long e = (long)blockIdx.x * 256 + threadIdx.x;
     const long n_w2 = (long)K * d_h;
     float g = 0.f;
@@ -237,34 +298,6 @@ __global__ __launch_bounds__(256) void train_w1_update_kernel(
     }
 }
 
-// ---- 5. loss = {lambda CE + (1 - lambda) MSE, CE, MSE}, fixed summation order -----------------
-__global__ __launch_bounds__(256) void train_loss_kernel(const float *__restrict__ loss_part, int B, float lambda,
-                                                         float *__restrict__ loss)
-{
-    __shared__ float red[2][256];
-    const int tid = threadIdx.x;
-    float ce = 0.f, mse = 0.f;
-    for (int b = tid; b < B; b += 256) {
-        ce += loss_part[2 * b];
-        mse += loss_part[2 * b + 1];
-    }
-    red[0][tid] = ce;
-    red[1][tid] = mse;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) {
-            red[0][tid] += red[0][tid + s];
-            red[1][tid] += red[1][tid + s];
-        }
-        __syncthreads();
-    }
-    if (tid == 0) {
-        loss[0] = lambda * red[0][0] + (1.0f - lambda) * red[1][0];
-        loss[1] = red[0][0];
-        loss[2] = red[1][0];
-    }
-}
-
 }  // namespace
 
 hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
@@ -297,13 +330,12 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     h.corr1 = a.corr1;
     h.corr2 = a.corr2;
     const long n_small = (long)a.K * a.d_h + a.K + a.d_h;
-    hipLaunchKernelGGL(train_small_update_kernel, dim3((unsigned)((n_small + 255) / 256)), dim3(256), 0, st, a.act,
+    hipLaunchKernelGGL(train_small_update_kernel, dim3((unsigned)((n_small + 255) / 256 + 1)), dim3(256), 0, st, a.act,
                        a.dact, a.dz, a.B, a.d_h, a.K, h, a.w2, a.m_w2, a.v_w2, a.b2, a.m_b2, a.v_b2, a.b1, a.m_b1,
-                       a.v_b1, a.g_w2, a.g_b2, a.g_b1);
+                       a.v_b1, a.g_w2, a.g_b2, a.g_b1, a.loss_part, a.lambda, a.loss);
     // W1 is last: the forward pass and the backward pass above read the old W1 / W2
     hipLaunchKernelGGL(train_w1_update_kernel, dim3((a.d + GN - 1) / GN, (a.d_h + GM - 1) / GM), dim3(256), 0, st,
                        a.x, a.dact, a.B, a.d, a.d_h, h, a.w1, a.m_w1, a.v_w1, a.g_w1);
-    hipLaunchKernelGGL(train_loss_kernel, dim3(1), dim3(256), 0, st, a.loss_part, a.B, a.lambda, a.loss);
     return hipGetLastError();
 }
 
