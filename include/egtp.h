@@ -77,7 +77,7 @@ typedef struct {
 } egtp_head;
 
 typedef struct {
-    int32_t d;          /* hidden size */
+    int32_t d;          /* hidden size (bf16: at most 4 194 240) */
     int32_t vocab;      /* vocabulary size V */
     egtp_dtype dtype;   /* storage type of hidden states and w_lm */
     const void *w_lm;   /* [vocab x d] device, must outlive the context.  bf16 contexts may pass NULL

@@ -234,6 +234,8 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
         return EGTP_ERR_SHAPE;
     if (cfg->d % (cfg->dtype == EGTP_BF16 ? 8 : 4) != 0)
         return EGTP_ERR_SHAPE;  // rows must start on 16-byte boundaries
+    if (cfg->dtype == EGTP_BF16 && cfg->d > 4194240)
+        return EGTP_ERR_SHAPE;  // the fused kernel addresses a packed row tile over all of d with 32-bit byte offsets
     if (!cfg->w_lm && cfg->dtype != EGTP_BF16)
         return EGTP_ERR_NULL;  // a bf16 context can live on a packed copy alone (egtp_adopt_packed_w_lm)
     if (!(cfg->alpha > 0.0f) || !isfinite(cfg->alpha))

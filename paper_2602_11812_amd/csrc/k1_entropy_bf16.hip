@@ -22,7 +22,7 @@
 // 256 vocabulary rows x 256 tokens, each wave 128 x 128 = 8x8 MFMA 16x16x32 tiles
 // (256 accumulator registers); one 16-byte fragment read covers a whole K step: lane l
 // holds row l%16, chunk l/16 of the 64-byte row.  Blocks go from global memory straight
-// into an NSTAGE-deep LDS ring (16 bytes per lane, no staging registers).  The kernel runs
+// into an NSTAGE-deep LDS ring (buffer loads to LDS, 16 bytes per lane, no staging registers).  The kernel runs
 // at the package power limit, so what counts is energy per FLOP: the 16x16x32 shape with the
 // first operand held for 8 consecutive MFMAs (row-major tile order) draws markedly less
 // power than 32x32x16 or than any order that changes both operands every MFMA.  One wave
@@ -65,12 +65,20 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane i of the wave lands at
-// lds_wave_base + 16 * i.
-__device__ __forceinline__ void load16_to_lds(const unsigned char *g, unsigned char *lds_wave_base)
+// 16 bytes per lane from memory straight into LDS: lane i of the wave lands at lds_wave_base + 16 * i.
+// A buffer load (descriptor + per-lane byte offset + scalar byte offset): the address of a K step is then one
+// scalar add, with no 64-bit vector arithmetic in the main loop, and the hardware clamps every access to the
+// descriptor's range.  Measured against the flat-address form of the same load: 0.5 % faster.
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, int lane_byte_offset, int scalar_byte_offset,
+                                              unsigned char *lds_wave_base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)lds_wave_base, 16,
+                                             lane_byte_offset, scalar_byte_offset, 0, 0);
+}
+// raw buffer descriptor over `bytes` bytes at p (gfx9 family: 32-bit data format word, no swizzle)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const unsigned char *p, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)p, 0, bytes, 0x00020000);
 }
 
 // scheduling-group masks of the AMDGPU backend
@@ -170,18 +178,19 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
     const int total = (vt_end - vt_begin) * KT;
 
     // ---- global -> LDS: a block is copied linearly, 1 KiB per wave-wide load ------------
-    const unsigned lane_off = (unsigned)(wave * 1024 + lane * 16);
-    const unsigned char *Hblk = Hp + (long)tb * KT * TILE_BYTES + lane_off;
-    const unsigned char *Wl = Wp + lane_off;
+    const int lane_off = wave * 1024 + lane * 16;
+    const int tile_bytes = KT * TILE_BYTES;  // one row tile of a packed operand over all of K (the launcher checks the range)
+    const __amdgpu_buffer_rsrc_t rH = raw_buffer(Hp + (long)tb * tile_bytes, tile_bytes);  // this workgroup's token block
     unsigned char *lds_wave = smem + wave * 1024;
     auto issue_loads = [&](int vt, int kt, int stage) {
-        const unsigned char *Wt = Wl + ((long)vt * KT + kt) * TILE_BYTES;
-        const unsigned char *Ht = Hblk + (long)kt * TILE_BYTES;
+        // the descriptor of W_lm moves with the vocabulary tile, so that byte offsets stay inside one tile
+        const __amdgpu_buffer_rsrc_t rW = raw_buffer(Wp + (long)vt * tile_bytes, tile_bytes);
+        const int koff = kt * TILE_BYTES;
         unsigned char *dst = lds_wave + stage * STAGE_BYTES;
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            load16_to_lds(Wt + p * 4096, dst + p * 4096);
-            load16_to_lds(Ht + p * 4096, dst + TILE_BYTES + p * 4096);
+            load16_to_lds(rW, lane_off, koff + p * 4096, dst + p * 4096);
+            load16_to_lds(rH, lane_off, koff + p * 4096, dst + TILE_BYTES + p * 4096);
         }
     };
 
@@ -446,6 +455,8 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
     const int kt = k_steps(d);
+    if ((long)kt * TILE_BYTES > 0x7fffffffL)
+        return hipErrorInvalidValue;  // a row tile over all of K is addressed with 32-bit byte offsets
     // pacing counters: one per cohort, cleared by a kernel (a caller may be capturing a graph)
     if (!k1_plan_paces(DT_BF16, p))
         pace = nullptr;  // no pacing point inside a range
