@@ -421,6 +421,47 @@ def test_deterministic_and_batch_invariant(gpu):
         assert rel_l2(one["pooled"][0], a["pooled"][s]) < 1e-5
 
 
+def test_two_contexts_overlap_on_two_streams(gpu):
+    """Two contexts, each with its own workspace, scoring on two streams at once (a serving engine with more
+    than one stream): every overlapped call gives, bit for bit, what the same call gives alone.  One of the two
+    shapes runs with the cohort pacing on, whose counters live in the workspace and whose waits are bounded, so
+    workgroups of the other launch sitting between a cohort's members may slow it down but change nothing."""
+    import torch
+    wa = _small_bf16(seed=201, B=9, d=32, V=128037, d_h=24, lengths=(400, 731, 290, 1, 512, 640, 77, 333, 516))
+    plan = gpu.egtp_launch_plan_query(gpu.EGTP_BF16, 32, 128037, wa.T)
+    assert plan.paced == 1 and plan.tiles_per_range >= 24          # one round of workgroups, six pacing points
+    wb = _small_bf16(seed=202, B=7, d=512, V=5000, d_h=64, lo=30, hi=500)
+    jobs = []
+    for w in (wa, wb):
+        sc = _scorer(gpu, w)
+        off = _offsets_on_gpu(gpu, sc, w.lengths)
+        hd = gpu.to_device(w.hidden)
+        sc.workspace(w.T, len(w.lengths))                            # allocated before any stream forks
+        alone = _np(sc.score(hd, off))
+        assert_egtp_close(alone, oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm,
+                                             oracle.Head(w.w1, w.w2)))
+        outs = [dict(entropy=torch.empty(w.T, dtype=torch.float32, device="cuda"),
+                     pooled=torch.empty(len(w.lengths), w.spec.d, dtype=torch.float32, device="cuda"),
+                     lse=torch.empty(len(w.lengths), dtype=torch.float32, device="cuda"),
+                     pred=torch.empty(len(w.lengths), dtype=torch.float32, device="cuda")) for _ in range(2)]
+        jobs.append((sc, hd, off, alone, outs, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for sc, hd, off, _, outs, st in jobs:
+            with torch.cuda.stream(st):
+                for o in outs:                                       # two calls back to back on each stream
+                    sc.score(hd, off, out=o)
+        torch.cuda.synchronize()
+        for _, _, _, alone, outs, _ in jobs:
+            for o in outs:
+                got = _np(o)
+                for k in alone:
+                    assert np.array_equal(got[k], alone[k]), (rep, k)
+                o["entropy"].fill_(float("nan"))
+                o["pooled"].fill_(float("nan"))
+        torch.cuda.synchronize()
+
+
 def test_vocabulary_permutation_invariance(gpu):
     w = _small_bf16(seed=23, B=2, d=128, V=1300, d_h=8)
     a = _run(gpu, w)
@@ -624,6 +665,37 @@ def test_mfma_probe_runs_and_checks_arguments(gpu):
             gpu.egtp_mfma_probe(sc.ctx, sink, kw["iters"], False, kw["launches"])
     with pytest.raises(gpu.EgtpError):
         gpu.egtp_mfma_probe(sc.ctx, sink[:1000], 10, False, 1)
+
+
+def test_hbm_read_probe_reads_every_word_once(gpu):
+    """The streaming-read measurement: the per-thread XOR words it leaves in its sink fold to the XOR of the
+    whole buffer (a piece read twice or skipped would break that, ragged 16-byte tail included), rates are
+    positive and finite, and bad arguments become status codes before any launch."""
+    import torch
+    sc = _scorer(gpu, wl.make(wl.SPECS["tiny"]))
+    nsink = gpu.egtp_hbm_read_probe_sink_bytes()
+    assert nsink == 8192 * 256 * 4
+    sink = torch.empty(nsink, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(11)
+    for nbytes in ((1 << 20), (1 << 20) + 16 * 12345, (64 << 20) + 16 * 7 + 8):
+        buf = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g)
+        r = gpu.egtp_hbm_read_probe(sc.ctx, buf, sink, 2)
+        assert r.shape == (2,) and (r > 0.0).all() and (r < 2.0e4).all(), r   # cache-resident sizes
+        torch.cuda.synchronize()
+        words = buf[:nbytes // 16 * 16].view(torch.int32).cpu().numpy()
+        want = int(np.bitwise_xor.reduce(words))
+        got = int(np.bitwise_xor.reduce(sink.view(torch.int32).cpu().numpy()))
+        assert got == want, nbytes
+    buf = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(gpu.EgtpError):
+        gpu.egtp_hbm_read_probe(sc.ctx, buf[:1000], sink, 1)          # under 1 MiB
+    with pytest.raises(gpu.EgtpError):
+        gpu.egtp_hbm_read_probe(sc.ctx, buf[8:], sink, 1)             # not 16-byte aligned
+    with pytest.raises(gpu.EgtpError):
+        gpu.egtp_hbm_read_probe(sc.ctx, buf, sink[:nsink - 4], 1)     # sink too small
+    for launches in (0, 65):
+        with pytest.raises(gpu.EgtpError):
+            gpu.egtp_hbm_read_probe(sc.ctx, buf, sink, launches)
 
 
 def test_head_keeps_the_pooled_vector_in_fp32(gpu):

@@ -118,3 +118,33 @@ def test_training_workspace_size_is_monotonic_and_rejects_bad_shapes(lib):
     assert f(16, 4094, 1024, 20) == 0        # feature size must be a multiple of 4
     assert f(16, 4096, 0, 20) == 0 and f(16, 4096, 1024, 0) == 0 and f(-1, 4096, 1024, 20) == 0
     assert f(16, 4096, 16385, 20) == 0 and f(16, 4096, 1024, 1025) == 0
+
+
+class _Plan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("tokens_per_block", "rows_per_tile", "token_blocks", "vocab_tiles",
+                                               "vocab_ranges", "tiles_per_range", "paced")]
+
+
+def test_launch_plan_query_needs_no_device_and_covers_the_vocabulary(lib):
+    """The plan the fused kernel would be launched with: every vocabulary tile belongs to exactly one range,
+    the token blocks cover the batch, and malformed shapes come back as status codes."""
+    q = lib.egtp_launch_plan_query
+    q.restype = ctypes.c_int
+    q.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.POINTER(_Plan)]
+    for dtype in (0, 1):
+        for d, V, T in ((4096, 151936, 137720), (4096, 151936, 512), (4096, 151936, 1), (64, 200, 10),
+                        (4096, 128037, 24576), (8192, 32000, 100000), (256, 257, 0)):
+            p = _Plan()
+            assert q(dtype, d, V, T, ctypes.byref(p)) == 0
+            assert p.tokens_per_block > 0 and p.rows_per_tile > 0
+            assert p.vocab_tiles == -(-V // p.rows_per_tile)
+            assert p.token_blocks == -(-T // p.tokens_per_block)
+            assert 1 <= p.vocab_ranges <= p.vocab_tiles
+            assert (p.vocab_ranges - 1) * p.tiles_per_range < p.vocab_tiles <= p.vocab_ranges * p.tiles_per_range
+            assert p.paced in (0, 1) and not (p.paced and (dtype == 0 or p.token_blocks < 8))
+    p = _Plan()
+    assert q(1, 4096, 151936, 137720, ctypes.byref(p)) == 0 and p.paced == 1     # the configuration that is timed
+    assert q(1, 4096, 151936, 137720, None) == 1
+    assert q(7, 4096, 151936, 10, ctypes.byref(p)) != 0
+    for d, V, T in ((0, 10, 10), (10, 0, 10), (10, 10, -1), (10, 10, 1 << 31)):
+        assert q(1, d, V, T, ctypes.byref(p)) != 0
