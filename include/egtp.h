@@ -26,7 +26,11 @@
  *   - Matrices are row-major, dense.  hidden is [T x d], w_lm is [vocab x d], both of
  *     egtp_config.dtype (bf16 = upper half of an fp32, or fp32).  Accumulation, entropies,
  *     pooled vectors, lse and predictions are fp32.  Row starts must be 16-byte aligned
- *     (bf16: d a multiple of 8; fp32: d a multiple of 4).
+ *     (bf16: d a multiple of 8; fp32: d a multiple of 4).  The LM-head contraction of Eq. 2 runs
+ *     on the bf16 matrix cores for both types: products of bf16 values are exact in the fp32
+ *     accumulators; an fp32 value enters as the exact sum of three bf16 pieces, and of the nine
+ *     piece products of w*h the six of relative size >= 2^-16 are accumulated (the rest is below
+ *     fp32's own rounding), so fp32 inputs give fp32-grade logits at six times the bf16 cost.
  *   - Ragged batches: offsets[B+1] int32, offsets[0] = 0, non-decreasing, offsets[B] = T.
  *     A repeated offset is an empty sequence: pooled = 0, lse = -inf, prediction = head(0).
  *   - Errors are return codes; on any error nothing has been launched.  B == 0 or T == 0 with
@@ -77,11 +81,11 @@ typedef struct {
 } egtp_head;
 
 typedef struct {
-    int32_t d;          /* hidden size (bf16: at most 4 194 240) */
+    int32_t d;          /* hidden size (bf16: at most 4 194 240; fp32: at most 699 040) */
     int32_t vocab;      /* vocabulary size V */
     egtp_dtype dtype;   /* storage type of hidden states and w_lm */
-    const void *w_lm;   /* [vocab x d] device, must outlive the context.  bf16 contexts may pass NULL
-                         * and live on a packed copy alone (egtp_adopt_packed_w_lm) */
+    const void *w_lm;   /* [vocab x d] device, must outlive the context.  May be NULL: the context then
+                         * lives on a packed copy alone (egtp_adopt_packed_w_lm) */
     float alpha;        /* pooling temperature, finite and > 0; 1.0f is Eq. 3 as printed */
     egtp_head head_len; /* EGTP: predicted total length */
     egtp_head head_rem; /* PLP: predicted remaining length; w1 == NULL means "use head_len" */
@@ -92,22 +96,22 @@ typedef struct {
 egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out);
 egtp_status egtp_destroy(egtp_ctx *ctx);
 
-/* The bf16 matrix-core kernel reads W_lm from a packed copy (tiles of 256 rows x 32 hidden
- * elements, contiguous per tile and K step).  egtp_pack_w_lm builds that copy once into
+/* The matrix-core kernel reads W_lm from a packed copy (tiles of 256 rows x 32 K elements of bf16,
+ * contiguous per tile and K step; 2 bytes per element of W_lm for bf16, 12 for fp32: six K segments
+ * of bf16 pieces).  egtp_pack_w_lm builds that copy once into
  * packed_dev (device memory of at least egtp_packed_w_lm_bytes(), 256-byte aligned, borrowed:
  * it must stay valid and unmodified while the context uses it; enqueued on `stream`, and later
  * scoring calls must be ordered after it).  Without it every scoring call re-packs W_lm into
  * its workspace first -- fine for large prefill batches, wasteful for decode steps.  Calling it
  * again re-packs (after w_lm changed); packed_dev == NULL forgets the copy.  Changing between
- * "packed" and "not packed" changes egtp_workspace_bytes().  fp32 contexts: bytes = 0,
- * packing is EGTP_ERR_DTYPE.  A context created with w_lm == NULL has nothing to pack from
- * (EGTP_ERR_NULL). */
+ * "packed" and "not packed" changes egtp_workspace_bytes().  A context created with
+ * w_lm == NULL has nothing to pack from (EGTP_ERR_NULL). */
 size_t egtp_packed_w_lm_bytes(const egtp_ctx *ctx);
 egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *stream);
 /* Registers a packed copy that already exists -- built earlier by egtp_pack_w_lm of a context with
  * the same d, vocab and dtype -- without touching it.  With it a context needs no row-major W_lm at
  * all: the Eq. 2 kernel only ever reads the packed copy, so a caller that keeps W_lm elsewhere (or
- * nowhere) saves 2 d vocab bytes.  Same alignment, size and lifetime rules as above; scoring
+ * nowhere) saves the d vocab elements of the row-major matrix.  Same alignment, size and lifetime rules as above; scoring
  * calls of a context that has neither w_lm nor a packed copy return EGTP_ERR_NULL. */
 egtp_status egtp_adopt_packed_w_lm(egtp_ctx *ctx, const void *packed_dev, size_t bytes);
 
@@ -255,7 +259,7 @@ egtp_status egtp_head_train_step(const egtp_head_train *head, const float *x, co
 /* Diagnostic: how the fused LM-head + entropy kernel (Eq. 2) would be launched for T tokens --
  * one workgroup per (block of tokens_per_block tokens, range of tiles_per_range vocabulary tiles of
  * rows_per_tile rows); each leaves one partial (max, sum, weighted sum) triple per token, merged
- * afterwards.  paced = 1 when the bf16 kernel's workgroups keep each other in step (ranges longer
+ * afterwards.  paced = 1 when the kernel's workgroups keep each other in step (ranges longer
  * than four tiles, at least eight token blocks).  Pure host arithmetic: no device, no context.  Tests use it to make sure
  * that a shape reaches the launch configuration they mean to cover. */
 typedef struct {

@@ -474,7 +474,7 @@ class Scorer:
         self.ctx = egtp_create(cfg)
         self._ws = None
         self._w_packed = None
-        if pack_w_lm and w_lm.dtype == torch.bfloat16:
+        if pack_w_lm:
             self._w_packed = torch.empty(egtp_packed_w_lm_bytes(self.ctx), dtype=torch.uint8, device="cuda")
             egtp_pack_w_lm(self.ctx, self._w_packed)
 

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libegtp.so")
 
-SOURCES = ["egtp_api.hip", "k1_plan.cpp", "k1_entropy_bf16.hip", "k1_aux.hip", "k1_entropy_f32.hip", "k2_pool.hip", "k3_head.hip", "k4_train.hip", "mfma_probe.hip", "hbm_probe.hip", "sched.cpp"]
+SOURCES = ["egtp_api.hip", "k1_plan.cpp", "k1_entropy_bf16.hip", "k1_aux.hip", "k2_pool.hip", "k3_head.hip", "k4_train.hip", "mfma_probe.hip", "hbm_probe.hip", "sched.cpp"]
 
 # packed-fp32 instruction selection is switched off for device code on purpose
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

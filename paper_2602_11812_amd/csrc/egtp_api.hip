@@ -58,8 +58,8 @@ struct Workspace {
     float *state_scale;  // [B]
     float *pool_part;    // [units_bound x d]
     float *act;          // [k splits x B x d_h_max]
-    unsigned char *hidden_packed;  // bf16 only: packed copy of this call's hidden states
-    unsigned char *w_packed;       // bf16 only, when no persistent packed W_lm was given
+    unsigned char *hidden_packed;  // packed copy of this call's hidden states
+    unsigned char *w_packed;       // when no persistent packed W_lm was given
     size_t bytes;
 };
 
@@ -80,13 +80,9 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     w.state_scale = cv.take<float>((size_t)B);
     w.pool_part = cv.take<float>((size_t)pool_units_bound(T, B) * (size_t)c.d);
     w.act = cv.take<float>(act_len > act_rem ? act_len : act_rem);
-    w.hidden_packed = nullptr;
-    w.w_packed = nullptr;
-    if (c.dtype == EGTP_BF16) {
-        w.hidden_packed = cv.take<unsigned char>(k1_packed_bytes(T, c.d));
-        if (!ctx->w_packed)
-            w.w_packed = cv.take<unsigned char>(k1_packed_bytes(c.vocab, c.d));
-    }
+    const int K = (int)k1_contraction_len(c.dtype, c.d);
+    w.hidden_packed = cv.take<unsigned char>(k1_packed_bytes(T, K));
+    w.w_packed = ctx->w_packed ? nullptr : cv.take<unsigned char>(k1_packed_bytes(c.vocab, K));
     w.bytes = cv.off;
     return w;
 }
@@ -129,6 +125,13 @@ egtp_status hip_fail(egtp_ctx *ctx, hipError_t e)
             return hip_fail(ctx, e_); \
     } while (0)
 
+// row-major operand -> the packed blocks the fused kernel reads (fp32: split into bf16 pieces on the way)
+hipError_t pack_rows(int dtype, const void *src, int64_t rows, int d, bool hidden_side, void *dst, hipStream_t st)
+{
+    return dtype == EGTP_BF16 ? k1_pack_rows_bf16(src, rows, d, dst, st)
+                              : k1_pack_rows_f32_split(src, rows, d, hidden_side, dst, st);
+}
+
 // Eq. 2 for T tokens: fused partials, then the per-token merge into `entropy` -- unless the caller merges
 // them itself (nsplit_left != NULL receives the number of ranges still to be merged).
 egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Workspace &w, float *entropy,
@@ -138,20 +141,15 @@ egtp_status run_entropy(egtp_ctx *ctx, const void *hidden, int64_t T, const Work
     const K1Plan p = k1_plan(c.dtype, T, c.d, c.vocab);
     const bool timed = ctx->prof_events && ctx->prof_count < ctx->prof_cap;
     const void *wp = ctx->w_packed;
-    if (c.dtype == EGTP_BF16) {
-        if (!wp) {  // no persistent packed W_lm: pack it for this call
-            EGTP_HIP(k1_pack_rows_bf16(c.w_lm, c.vocab, c.d, w.w_packed, st));
-            wp = w.w_packed;
-        }
-        EGTP_HIP(k1_pack_rows_bf16(hidden, T, c.d, w.hidden_packed, st));
+    if (!wp) {  // no persistent packed W_lm: pack it for this call
+        EGTP_HIP(pack_rows(c.dtype, c.w_lm, c.vocab, c.d, false, w.w_packed, st));
+        wp = w.w_packed;
     }
+    EGTP_HIP(pack_rows(c.dtype, hidden, T, c.d, true, w.hidden_packed, st));
     if (timed)
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count], st));
-    if (c.dtype == EGTP_BF16) {
-        EGTP_HIP(k1_entropy_bf16(w.hidden_packed, wp, T, c.d, c.vocab, p, w.k1_part, w.k1_pace, st));
-    } else {
-        EGTP_HIP(k1_entropy_f32(hidden, c.w_lm, T, c.d, c.vocab, p, w.k1_part, st));
-    }
+    EGTP_HIP(k1_entropy_bf16(w.hidden_packed, wp, T, (int)k1_contraction_len(c.dtype, c.d), c.vocab, p, w.k1_part,
+                             w.k1_pace, st));
     if (timed) {
         EGTP_HIP(hipEventRecord(ctx->prof_events[2 * ctx->prof_count + 1], st));
         ++ctx->prof_count;
@@ -234,10 +232,8 @@ egtp_status egtp_create(const egtp_config *cfg, egtp_ctx **out)
         return EGTP_ERR_SHAPE;
     if (cfg->d % (cfg->dtype == EGTP_BF16 ? 8 : 4) != 0)
         return EGTP_ERR_SHAPE;  // rows must start on 16-byte boundaries
-    if (cfg->dtype == EGTP_BF16 && cfg->d > 4194240)
-        return EGTP_ERR_SHAPE;  // the fused kernel addresses a packed row tile over all of d with 32-bit byte offsets
-    if (!cfg->w_lm && cfg->dtype != EGTP_BF16)
-        return EGTP_ERR_NULL;  // a bf16 context can live on a packed copy alone (egtp_adopt_packed_w_lm)
+    if (k1_contraction_len(cfg->dtype, cfg->d) > K1_MAX_CONTRACTION)
+        return EGTP_ERR_SHAPE;  // the fused kernel addresses a packed row tile over all of K with 32-bit byte offsets
     if (!(cfg->alpha > 0.0f) || !isfinite(cfg->alpha))
         return EGTP_ERR_ALPHA;
     egtp_status s = check_head(cfg->head_len);
@@ -392,7 +388,7 @@ egtp_status egtp_launch_plan_query(egtp_dtype dtype, int32_t d, int32_t vocab, i
     out->vocab_tiles = p.ntiles_v;
     out->vocab_ranges = p.nsplit;
     out->tiles_per_range = p.tiles_per_split;
-    out->paced = T > 0 && k1_plan_paces(dtype, p) ? 1 : 0;
+    out->paced = T > 0 && k1_plan_paces(p) ? 1 : 0;
     return EGTP_OK;
 }
 
@@ -443,9 +439,9 @@ int egtp_last_hip_error(const egtp_ctx *ctx) { return ctx ? ctx->last_hip_error 
 
 size_t egtp_packed_w_lm_bytes(const egtp_ctx *ctx)
 {
-    if (!ctx || ctx->cfg.dtype != EGTP_BF16)
+    if (!ctx)
         return 0;
-    return k1_packed_bytes(ctx->cfg.vocab, ctx->cfg.d);
+    return k1_packed_bytes(ctx->cfg.vocab, (int)k1_contraction_len(ctx->cfg.dtype, ctx->cfg.d));
 }
 
 egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *stream)
@@ -456,13 +452,12 @@ egtp_status egtp_pack_w_lm(egtp_ctx *ctx, void *packed_dev, size_t bytes, void *
         ctx->w_packed = nullptr;
         return EGTP_OK;
     }
-    if (ctx->cfg.dtype != EGTP_BF16)
-        return EGTP_ERR_DTYPE;
     if (!ctx->cfg.w_lm)
         return EGTP_ERR_NULL;  // nothing to pack from
     if (((uintptr_t)packed_dev % ALIGN) != 0 || bytes < egtp_packed_w_lm_bytes(ctx))
         return EGTP_ERR_WORKSPACE;
-    EGTP_HIP(k1_pack_rows_bf16(ctx->cfg.w_lm, ctx->cfg.vocab, ctx->cfg.d, packed_dev, (hipStream_t)stream));
+    EGTP_HIP(pack_rows(ctx->cfg.dtype, ctx->cfg.w_lm, ctx->cfg.vocab, ctx->cfg.d, false, packed_dev,
+                       (hipStream_t)stream));
     ctx->w_packed = packed_dev;
     return EGTP_OK;
 }
@@ -471,8 +466,6 @@ egtp_status egtp_adopt_packed_w_lm(egtp_ctx *ctx, const void *packed_dev, size_t
 {
     if (!ctx || !packed_dev)
         return EGTP_ERR_NULL;
-    if (ctx->cfg.dtype != EGTP_BF16)
-        return EGTP_ERR_DTYPE;
     if (((uintptr_t)packed_dev % ALIGN) != 0 || bytes < egtp_packed_w_lm_bytes(ctx))
         return EGTP_ERR_WORKSPACE;
     ctx->w_packed = packed_dev;
@@ -499,7 +492,7 @@ egtp_status egtp_build_offsets(egtp_ctx *ctx, const int32_t *lengths_dev, int32_
 
 namespace {
 
-// a bf16 context without the row-major W_lm can only score from a packed copy
+// a context without the row-major W_lm can only score from a packed copy
 bool lm_head_missing(const egtp_ctx *ctx) { return !ctx->cfg.w_lm && !ctx->w_packed; }
 
 egtp_status score_impl(egtp_ctx *ctx, const void *hidden, const int32_t *offsets_dev,

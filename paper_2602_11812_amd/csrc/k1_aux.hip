@@ -1,5 +1,7 @@
-// Kernels around the bf16 fused entropy kernel (Eq. 2): packing of row-major bf16 operands into
-// the block layout the fused kernel reads, and the merge of its partial statistics into H.
+// Kernels around the fused entropy kernel (Eq. 2): packing of row-major operands (bf16 as they are, fp32
+// as six K segments of bf16 pieces) into the block layout the fused kernel reads, and the merge of its
+// partial statistics into H.
+#include "bf16_split.h"
 #include "k1_common.h"
 
 namespace egtp {
@@ -121,12 +123,86 @@ __global__ __launch_bounds__(256) void pack_rows_bf16_kernel(const unsigned char
     }
 }
 
+// fp32 operands.  With w = w0 + w1 + w2 and h = h0 + h1 + h2 (bf16 pieces, leading piece first), w.h is
+// the sum of nine piece products of relative size 2^-8(i+j); the three smallest (i + j >= 3, below
+// 2^-24) are dropped, and the other six are laid side by side along K -- one bf16 contraction of length
+// 6 * dseg, dseg = d rounded up to whole 32-element blocks.  Segment s multiplies piece SPLIT_W[s] of W_lm
+// with piece SPLIT_H[s] of the hidden state; the smallest products come first, so the fp32 accumulators
+// meet the terms in ascending order of magnitude.
+__device__ constexpr int SPLIT_W[K1_SPLIT_TERMS] = {2, 1, 0, 1, 0, 0};
+__device__ constexpr int SPLIT_H[K1_SPLIT_TERMS] = {0, 1, 2, 0, 1, 0};
+
+// Packs rows of a row-major fp32 matrix src[R x d] (d % 4 == 0) into the six segments of one operand
+// side.  Thread layout as in the bf16 kernel, over the `kseg` blocks of ONE segment: every thread reads
+// its 8 values once, splits them, and stores the piece each segment asks for.
+template <bool HIDDEN_SIDE>
+__global__ __launch_bounds__(256) void pack_rows_f32_split_kernel(const float *__restrict__ src, long R, int d,
+                                                                  int kseg, int rows_per_wg,
+                                                                  unsigned char *__restrict__ dst)
+{
+    const long tile = blockIdx.x;
+    const int c32 = threadIdx.x & 31;
+    const int rsub = threadIdx.x >> 5;
+    const int kk = blockIdx.y * 8 + (c32 >> 2);  // block inside a segment
+    const int chunk = c32 & 3;
+    if (kk >= kseg)
+        return;
+    const long k_elem = (long)kk * BK + chunk * 8;
+    const long KT = (long)K1_SPLIT_TERMS * kseg;
+    const int r0 = blockIdx.z * rows_per_wg;
+    for (int r = r0 + rsub; r < r0 + rows_per_wg; r += 8) {
+        const long row = tile * 256 + r;
+        float4 lo4 = make_float4(0.f, 0.f, 0.f, 0.f), hi4 = lo4;
+        if (row < R) {  // d % 4 == 0: a group of four lies wholly inside a row or wholly past its end
+            if (k_elem < d)
+                lo4 = *(const float4 *)(src + row * d + k_elem);
+            if (k_elem + 4 < d)
+                hi4 = *(const float4 *)(src + row * d + k_elem + 4);
+        }
+        const float f[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        unsigned pc[3][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            split3_bits(f[i], pc[0][i], pc[1][i], pc[2][i]);
+        uint4 q[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+            q[p] = make_uint4((pc[p][0] >> 16) | pc[p][1], (pc[p][2] >> 16) | pc[p][3], (pc[p][4] >> 16) | pc[p][5],
+                              (pc[p][6] >> 16) | pc[p][7]);
+        const int in_block = r * ROW_BYTES + ((chunk ^ swizzle_key(r)) << 4);
+#pragma unroll
+        for (int s = 0; s < K1_SPLIT_TERMS; ++s) {
+            const int piece = HIDDEN_SIDE ? SPLIT_H[s] : SPLIT_W[s];
+            *(uint4 *)(dst + (tile * KT + (long)s * kseg + kk) * (long)TILE_BYTES + in_block) = q[piece];
+        }
+    }
+}
+
 }  // namespace
 
-size_t k1_packed_bytes(int64_t rows, int d)
+hipError_t k1_pack_rows_f32_split(const void *src, int64_t rows, int d, bool hidden_side, void *dst, hipStream_t st)
+{
+    if (rows <= 0)
+        return hipSuccess;
+    const long tiles = (rows + 255) / 256;
+    const int kseg = k1_split_segment(d) / BK;
+    if (tiles > 0x7fffffffL || k_steps((int)k1_contraction_len(DT_F32, d)) != K1_SPLIT_TERMS * kseg)
+        return hipErrorInvalidValue;
+    const int rows_per_wg = tiles * ((kseg + 7) / 8) >= 1024 ? 256 : 32;
+    const dim3 grid((unsigned)tiles, (kseg + 7) / 8, 256 / rows_per_wg);
+    if (hidden_side)
+        hipLaunchKernelGGL(pack_rows_f32_split_kernel<true>, grid, dim3(256), 0, st, (const float *)src, (long)rows,
+                           d, kseg, rows_per_wg, (unsigned char *)dst);
+    else
+        hipLaunchKernelGGL(pack_rows_f32_split_kernel<false>, grid, dim3(256), 0, st, (const float *)src, (long)rows,
+                           d, kseg, rows_per_wg, (unsigned char *)dst);
+    return hipGetLastError();
+}
+
+size_t k1_packed_bytes(int64_t rows, int K)
 {
     const int64_t tiles = (rows + 255) / 256;
-    const int64_t kt = k_steps(d);
+    const int64_t kt = k_steps(K);
     return (size_t)(tiles * kt) * TILE_BYTES;
 }
 

@@ -14,6 +14,9 @@ constexpr float NEG_BIG = -1.0e30f;
 constexpr float LOG2E = 1.4426950408889634f;
 static_assert(BK == 32 && TILE_BYTES == K1_PACK_BLOCK_BYTES, "packed block geometry");
 
+// Streaming statistics of a set of logits z against a reference m kept in log2 units (m = max z * log2 e,
+// rounded once; any reference not far below the true maximum serves):
+//   S = sum 2^(z log2 e - m),   U = sum 2^(z log2 e - m) (z log2 e - m);   H = ln S - U ln 2 / S.
 struct Stats {
     float m, S, U;
 };
@@ -34,7 +37,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ Stats merge(Stats a, Stats b)
 {
     float M = fmaxf(a.m, b.m);
-    float da = (a.m - M) * LOG2E, db = (b.m - M) * LOG2E;
+    float da = a.m - M, db = b.m - M;  // references are in log2 units already
     float sa = fast_exp2(da), sb = fast_exp2(db);
     Stats r;
     r.m = M;

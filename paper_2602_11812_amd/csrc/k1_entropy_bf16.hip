@@ -1,10 +1,12 @@
-// Fused LM-head contraction + streaming entropy for bf16 inputs on gfx950 (Eq. 2).
+// Fused LM-head contraction + streaming entropy on the bf16 matrix cores of gfx950 (Eq. 2).  bf16 inputs
+// are contracted as they are; fp32 inputs arrive split into bf16 pieces laid side by side along K (see the
+// packing kernels), so the same kernel gives fp32-grade logits from a contraction six times as long.
 //
 // logits^T = W_lm . hidden^T is computed tile by tile on the bf16 matrix cores with the
 // vocabulary as the MFMA row dimension and the tokens as its column dimension.  In the
 // 16x16 accumulator layout a lane holds rows 4*(l/16)+i of column l%16, i.e. logits of ONE
 // token (its column), so the softmax statistics of a token
-//     m = max z,  S = sum e^{z-m},  U = sum e^{z-m} (z-m) log2(e)
+//     m = max z (kept in log2 units),  S = sum e^{z-m},  U = sum e^{z-m} (z-m) log2(e)
 // are carried in registers, lane-private, across the whole vocabulary sweep, and the four
 // lanes and two waves that share a token are only combined once at the end.  Logits never
 // leave the register file:  H = ln S - U ln2 / S  is finished by the merge kernel from one
@@ -15,7 +17,7 @@
 // MFMA fragment reads are free of bank conflicts).  A K step of a tile is then one contiguous
 // 16 KiB read, which is what HBM and the Infinity Cache want; reading 64-byte row pieces
 // with a row stride of 2d bytes from the row-major matrices stalls the ring on DRAM page
-// misses.  pack_rows_bf16 builds the packed copy (W_lm once, hidden states once per call;
+// misses.  The packing kernels build the packed copy (W_lm once, hidden states once per call;
 // rows are zero-padded to whole blocks, K to an even number of blocks).
 //
 // Workgroup = 256 threads = 4 waves (2 along vocabulary x 2 along tokens), macro tile
@@ -102,14 +104,18 @@ __device__ __forceinline__ void fold16(const float (&zin)[16], Stats &st, int ro
         mx = fmaxf(mx, z[i]);
     if (MASK && !(mx > NEG_BIG))
         return;  // every row of this lane is masked: nothing to add (and no reference maximum yet)
-    if (mx > st.m) {  // new running maximum: rescale what has been summed so far
-        float dl = (st.m - mx) * LOG2E;
+    // The reference lives in log2 units, r = fl(max z * log2 e): every exponent is then ONE fused
+    // multiply-add z * log2 e - r (exact product, one rounding of a small result) and re-referencing is an
+    // exact difference of two r, so the precision does not degrade with the magnitude of the logits.
+    const float r = mx * LOG2E;
+    if (r > st.m) {  // new running reference: rescale what has been summed so far
+        float dl = st.m - r;
         float sc = fast_exp2(dl);
         st.U = (st.U + dl * st.S) * sc;
         st.S = st.S * sc;
-        st.m = mx;
+        st.m = r;
     }
-    const float mc = -st.m * LOG2E;
+    const float mc = -st.m;
     float S0 = 0.f, S1 = 0.f, U0 = 0.f, U1 = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
@@ -445,7 +451,7 @@ __global__ __launch_bounds__(256, 1) void k1_entropy_bf16_kernel(
 
 }  // namespace
 
-hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
+hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int K, int V,
                            const K1Plan &p, float *part, int *pace, hipStream_t st)
 {
     constexpr int NSTAGE = 4;
@@ -459,11 +465,11 @@ hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int6
     const long units = (long)p.ntb * p.nsplit;
     if (units <= 0 || units > 0x7fffffffL)
         return hipErrorInvalidValue;
-    const int kt = k_steps(d);
+    const int kt = k_steps(K);
     if ((long)kt * TILE_BYTES > 0x7fffffffL)
         return hipErrorInvalidValue;  // a row tile over all of K is addressed with 32-bit byte offsets
     // pacing counters: one per cohort, cleared by a kernel (a caller may be capturing a graph)
-    if (!k1_plan_paces(DT_BF16, p))
+    if (!k1_plan_paces(p))
         pace = nullptr;  // no pacing point inside a range
     if (pace != nullptr) {
         const int n = XCDS * k1_pace_cohorts(units);

@@ -5,8 +5,7 @@
 namespace egtp {
 
 // ---- geometry of the fused entropy kernel ------------------------------------------------
-static constexpr int BF16_TB = 256, BF16_TV = 256, BF16_TARGET_UNITS = 8192;
-static constexpr int F32_TB = 64, F32_TV = 64, F32_TARGET_UNITS = 1024;
+static constexpr int TB = 256, TV = 256, TARGET_UNITS = 8192;
 
 // compute units of the device the work is spread over (MI355X)
 static constexpr int NUM_CUS = 256;
@@ -15,10 +14,10 @@ static constexpr int NSPLIT_SLACK = 8;  // how far above the minimum the number 
 K1Plan k1_plan(int dtype, int64_t T, int d, int V)
 {
     K1Plan p;
-    const bool bf = dtype == DT_BF16;
-    p.tb_tokens = bf ? BF16_TB : F32_TB;
-    p.tile_v = bf ? BF16_TV : F32_TV;
-    const int target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    p.tb_tokens = TB;
+    p.tile_v = TV;
+    const int target = TARGET_UNITS;
+    const long dk = k1_contraction_len(dtype, d);  // what a K sweep runs over
     p.ntb = (int)((T + p.tb_tokens - 1) / p.tb_tokens);
     p.ntiles_v = (V + p.tile_v - 1) / p.tile_v;
     int ns0 = p.ntb > 0 ? (target + p.ntb - 1) / p.ntb : 1;
@@ -30,10 +29,10 @@ K1Plan k1_plan(int dtype, int64_t T, int d, int V)
         // A small batch: even one range per vocabulary tile gives fewer workgroups than asked for.  What
         // counts then is the number of rounds the compute units need and what every workgroup pays to
         // start and finish (filling the load ring, the final merge and stores: about START_STEPS K steps
-        // of a sweep of 2 ceil(d / 64) steps per tile).  512 tokens against 594 tiles are 1188 single-tile
+        // of a sweep of 2 ceil(K / 64) steps per tile).  512 tokens against 594 tiles are 1188 single-tile
         // workgroups = 5 rounds of starts, or 238 workgroups of 5 tiles each = one round of the same length.
         constexpr double START_STEPS = 6.0;
-        const double start_tiles = START_STEPS / (2.0 * ((d + 63) / 64));
+        const double start_tiles = START_STEPS / (2.0 * (double)((dk + 63) / 64));
         double best_cost = 0.0;
         for (int tps = 1; tps <= p.ntiles_v && tps <= 64; ++tps) {
             const int nsplit = (p.ntiles_v + tps - 1) / tps;
@@ -73,23 +72,21 @@ K1Plan k1_plan(int dtype, int64_t T, int d, int V)
 
 size_t k1_partial_floats(const K1Plan &p, int64_t T) { return (size_t)3 * (size_t)p.nsplit * (size_t)T; }
 
-size_t k1_partial_floats_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
+size_t k1_partial_floats_bound(int /*dtype*/, int64_t T, int /*d*/, int /*V*/)
 {
     // nsplit(T') <= target / ntb(T') + 1 + NSPLIT_SLACK, so
     // nsplit(T') * T' <= (target + (1 + NSPLIT_SLACK) * ntb(T')) * tb_tokens for every T' <= T
-    const bool bf = dtype == DT_BF16;
-    const int64_t tbk = bf ? BF16_TB : F32_TB;
-    const int64_t target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const int64_t tbk = TB;
+    const int64_t target = TARGET_UNITS;
     const int64_t ntb = (T + tbk - 1) / tbk;
     return (size_t)3 * (size_t)((target + (1 + NSPLIT_SLACK) * ntb) * tbk);
 }
 
-size_t k1_pace_ints_bound(int dtype, int64_t T, int /*d*/, int /*V*/)
+size_t k1_pace_ints_bound(int /*dtype*/, int64_t T, int /*d*/, int /*V*/)
 {
     // units(T') = ntb(T') * nsplit(T') <= target + (1 + NSPLIT_SLACK) * ntb(T)
-    const bool bf = dtype == DT_BF16;
-    const int64_t tbk = bf ? BF16_TB : F32_TB;
-    const int64_t target = bf ? BF16_TARGET_UNITS : F32_TARGET_UNITS;
+    const int64_t tbk = TB;
+    const int64_t target = TARGET_UNITS;
     const int64_t ntb = (T + tbk - 1) / tbk;
     return (size_t)8 * (size_t)k1_pace_cohorts((long)(target + (1 + NSPLIT_SLACK) * ntb));
 }

@@ -14,6 +14,7 @@
 // fp32, so three MFMAs per weight fragment accumulate the same products an fp32 dot product
 // would, in fp32.  Fragments come straight from global memory: a lane's 8 K-elements are 16
 // contiguous bytes of a weight row and 32 contiguous bytes of a pooled row.
+#include "bf16_split.h"
 #include "kernels.h"
 #include "partial_planes.h"
 #include "wave_reduce.h"
@@ -120,11 +121,7 @@ __device__ __forceinline__ void split3(const float (&f)[8], bf16x8 &hi, bf16x8 &
     unsigned h[8], m[8], l[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        h[i] = __float_as_uint(f[i]) & 0xffff0000u;
-        const float r1 = f[i] - __uint_as_float(h[i]);
-        m[i] = __float_as_uint(r1) & 0xffff0000u;
-        const float r2 = r1 - __uint_as_float(m[i]);
-        l[i] = __float_as_uint(r2) & 0xffff0000u;
+        split3_bits(f[i], h[i], m[i], l[i]);
     }
     u32x4 ph, pm, pl;
 #pragma unroll

@@ -39,23 +39,24 @@ inline hipError_t raise_dynamic_lds_limit(const void *kernel, int bytes, DeviceM
     return e;
 }
 
-// Packed operand layout of the bf16 matrix-core kernel: blocks of 256 rows x K1_PACK_K
+// Packed operand layout of the matrix-core kernel: blocks of 256 rows x K1_PACK_K bf16
 // elements (K1_PACK_BLOCK_BYTES each), block (row tile, K step) at index tile * steps + step with
-// steps = 2 * ceil(d / (2 K)) (an even number), stored in LDS-image order; rows and K zero-padded
-// to whole blocks.
+// steps = 2 * ceil(K / (2 K1_PACK_K)) (an even number), stored in LDS-image order; rows and K zero-padded
+// to whole blocks.  K is the contraction length the kernel sees: d for bf16 operands,
+// k1_contraction_len(DT_F32, d) for fp32 operands split into bf16 pieces.
 constexpr int K1_PACK_K = 32;
 constexpr int K1_PACK_BLOCK_BYTES = 256 * K1_PACK_K * 2;
-size_t k1_packed_bytes(int64_t rows, int d);
+size_t k1_packed_bytes(int64_t rows, int K);
 hipError_t k1_pack_rows_bf16(const void *src, int64_t rows, int d, void *dst, hipStream_t st);
+// fp32 rows (d % 4 == 0) into the six K segments of the W_lm side or of the hidden-state side
+hipError_t k1_pack_rows_f32_split(const void *src, int64_t rows, int d, bool hidden_side, void *dst,
+                                  hipStream_t st);
 
-// Eq. 2, fused: partial (max, sum e^{z-m}, sum e^{z-m}(z-m) log2 e) per token and vocabulary range.
-// bf16: both operands in the packed layout; `pace`: k1_pace_ints_bound ints of scratch (contents
-// do not matter on entry), or NULL to run without pacing.
-hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int d, int V,
+// Eq. 2, fused: partial (m = max z log2 e, sum e^{z-m}, sum e^{z-m}(z-m) log2 e) per token and vocabulary range.
+// Both operands in the packed layout, contraction length K; `pace`: k1_pace_ints_bound ints of scratch
+// (contents do not matter on entry), or NULL to run without pacing.
+hipError_t k1_entropy_bf16(const void *hidden_packed, const void *w_packed, int64_t T, int K, int V,
                            const K1Plan &p, float *part, int *pace, hipStream_t st);
-// fp32 inputs (row-major), plain fp32 FMAs
-hipError_t k1_entropy_f32(const void *hidden, const void *w_lm, int64_t T, int d, int V,
-                          const K1Plan &p, float *part, hipStream_t st);
 // merges the nsplit partial triples of each token in a fixed order; entropy[t] = ln S - U/S
 hipError_t k1_merge(const float *part, int nsplit, int64_t T, float *entropy, hipStream_t st);
 

@@ -323,13 +323,18 @@ void plan_checks()
         }
     // the paced configuration is the one with more than K1_PACE_TILES tiles per range
     const K1Plan serving = k1_plan(DT_BF16, 137720, 4096, 151936);
-    CHECK(serving.tiles_per_split > K1_PACE_TILES && k1_plan_paces(DT_BF16, serving));
-    CHECK(!k1_plan_paces(DT_F32, serving));
+    CHECK(serving.tiles_per_split > K1_PACE_TILES && k1_plan_paces(serving));
+    // fp32 operands run the same kernel over a contraction six times as long, in whole 32-element segments
+    CHECK(k1_contraction_len(DT_BF16, 4096) == 4096 && k1_contraction_len(DT_F32, 4096) == 6 * 4096);
+    CHECK(k1_contraction_len(DT_F32, 4) == 6 * 32 && k1_contraction_len(DT_F32, 36) == 6 * 64);
+    CHECK(k1_contraction_len(DT_F32, 699040) <= K1_MAX_CONTRACTION && k1_contraction_len(DT_F32, 699044) > K1_MAX_CONTRACTION);
+    const K1Plan serving_f32 = k1_plan(DT_F32, 137720, 4096, 151936);
+    CHECK(serving_f32.nsplit == serving.nsplit && serving_f32.tb_tokens == serving.tb_tokens);
     // 512 decode tokens: two token blocks, and one round of workgroups rather than five rounds of single tiles
     const K1Plan decode = k1_plan(DT_BF16, 512, 4096, 151936);
     CHECK(decode.ntb == 2 && (long)decode.ntb * decode.nsplit <= 256 && decode.tiles_per_split == 5);
     const K1Plan one_tile = k1_plan(DT_BF16, 10, 64, 200);
-    CHECK(one_tile.nsplit == 1 && one_tile.tiles_per_split == 1 && !k1_plan_paces(DT_BF16, one_tile));
+    CHECK(one_tile.nsplit == 1 && one_tile.tiles_per_split == 1 && !k1_plan_paces(one_tile));
 }
 
 }  // namespace

@@ -58,6 +58,51 @@ def test_tiny_fp32_end_to_end(gpu):
     assert got["offsets"].tolist() == [0, 17, 81, 181, 309]
     want = oracle.egtp(w.hidden, off, w.w_lm, oracle.Head(w.w1, w.w2))
     assert_egtp_close(got, want)
+    assert np.abs(got["entropy"] - want.entropy).max() <= 2e-5        # fp32 inputs: fp32-grade, not bf16-grade
+
+
+def _fp32_case(seed, lengths, d, V):
+    return wl.make(wl.scaled(wl.SPECS["tiny"], seed=seed, B=len(lengths), d=d, V=V, d_h=16, lengths=tuple(lengths)))
+
+
+def test_fp32_inputs_integer_logits_are_exact(gpu):
+    """fp32 operands go through the bf16 matrix cores as sums of bf16 pieces.  With 10-bit integer weights and
+    11-bit integer activations (times a power of two) every piece product and every partial sum is an integer
+    below 2^24, so the logits have to come out exactly, whatever the order of the additions: what is left is the
+    fp32 evaluation of the softmax statistics.  Each value needs two pieces, so a lost cross product (second piece
+    times second piece: a few units of 2^-12 on logits that differ by a few units) shows at once."""
+    w = _fp32_case(seed=301, lengths=(130, 1, 169), d=8, V=700)
+    rng = np.random.default_rng(301)
+    w.w_lm = rng.integers(512, 520, size=(700, 8)).astype(np.float32)
+    w.hidden = (rng.integers(1024, 2048, size=(w.T, 8)).astype(np.float32) * np.float32(2.0 ** -12))
+    assert (w.w_lm.astype(np.float64) @ w.hidden.astype(np.float64).T).max() * 2 ** 12 < 2 ** 24
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert 0.5 < want.entropy.min() and want.entropy.max() < np.log(700) - 0.01      # neither peaked nor flat
+    err = np.abs(got["entropy"] - want.entropy).max()
+    assert err <= 2e-5, err
+    assert_egtp_close(got, want)
+
+
+@pytest.mark.parametrize("side", ["w_lm", "hidden"])
+def test_fp32_inputs_keep_every_mantissa_bit(gpu, side):
+    """One operand is a 0/1 selection matrix, the other holds values near 1000 with full 24-bit mantissas: a
+    logit is then one element of that operand, exact only if all three of its bf16 pieces arrive (the last
+    piece of a value near 1000 is worth up to 0.015; the logits of a token differ by about one)."""
+    n = 300
+    w = _fp32_case(seed=302, lengths=(200, 100), d=n, V=n)
+    rng = np.random.default_rng(302 + (side == "hidden"))
+    full = (1000.0 + rng.standard_normal((n, n))).astype(np.float32)
+    assert np.any(full.view(np.uint32) & 0xff)                                        # low mantissa bits in use
+    eye = np.eye(n, dtype=np.float32)
+    if side == "w_lm":
+        w.w_lm, w.hidden = full, eye[rng.integers(0, n, size=w.T)]                   # logits of token t: a column of W_lm
+    else:
+        w.w_lm, w.hidden = eye, full[:w.T].copy()                                     # logits of token t: its own hidden state
+    got = _run(gpu, w)
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(w.lengths), w.w_lm, oracle.Head(w.w1, w.w2))
+    err = np.abs(got["entropy"] - want.entropy).max()
+    assert err <= 2e-5, err
 
 
 def test_offsets_and_segment_ids_bit_exact(gpu):

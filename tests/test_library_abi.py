@@ -76,8 +76,10 @@ def test_create_rejects_bad_configs_without_a_device(lib):
     assert create(cfg(d=0)) == 2
     assert create(cfg(d=100)) == 2                  # bf16 rows must be 16-byte aligned
     assert create(cfg(vocab=-5)) == 2
-    assert create(cfg(w_lm=None, dtype=0, d=256)) == 1   # fp32 contexts read the row-major W_lm
-    assert create(cfg(w_lm=None)) in (0, 6)              # bf16 ones may live on a packed copy alone
+    assert create(cfg(w_lm=None, dtype=0, d=256)) in (0, 6)   # a context may live on a packed copy alone
+    assert create(cfg(w_lm=None)) in (0, 6)
+    assert create(cfg(dtype=0, d=699044)) == 2                # fp32: six bf16 segments must fit the kernel's reach
+    assert create(cfg(dtype=0, d=699040)) in (0, 6)
     assert create(cfg(alpha=0.0)) == 8
     assert create(cfg(alpha=float("nan"))) == 8
     assert create(cfg(alpha=float("inf"))) == 8
@@ -141,7 +143,7 @@ def test_launch_plan_query_needs_no_device_and_covers_the_vocabulary(lib):
             assert p.token_blocks == -(-T // p.tokens_per_block)
             assert 1 <= p.vocab_ranges <= p.vocab_tiles
             assert (p.vocab_ranges - 1) * p.tiles_per_range < p.vocab_tiles <= p.vocab_ranges * p.tiles_per_range
-            assert p.paced in (0, 1) and not (p.paced and (dtype == 0 or p.token_blocks < 8))
+            assert p.paced in (0, 1) and not (p.paced and p.token_blocks < 8)
     p = _Plan()
     assert q(1, 4096, 151936, 137720, ctypes.byref(p)) == 0 and p.paced == 1     # the configuration that is timed
     assert q(1, 4096, 151936, 137720, None) == 1
