@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix-core peak (what fp32 inputs would be priced against)
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E peak
 
 
@@ -254,6 +255,9 @@ def main() -> int:
     ap.add_argument("--workload", default="serving", choices=["serving", "mid", "plp_decode", "rl", "pool", "train"],
                     help="serving = the workload the headline metric is quoted on (default)")
     ap.add_argument("--train-batch", type=int, default=16, help="samples per step of --workload train")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"],
+                    help="storage type of hidden states and W_lm for --workload serving / mid (bf16 = the headline "
+                         "configuration; f32 = the same shapes with fp32 inputs, split into bf16 pieces on the way in)")
     ap.add_argument("--oracle-tokens", type=int, default=640, help="tokens of the CPU-baseline sample (0 = skip)")
     ap.add_argument("--graph", action="store_true",
                     help="--workload plp_decode: replay the decode steps from a captured HIP graph")
@@ -285,6 +289,9 @@ def main() -> int:
     if args.workload == "pool":
         return bench_pool(args, gpu, wl, np, torch)
     spec = wl.SPECS[args.workload]
+    f32 = args.dtype == "f32"
+    if f32:
+        spec = wl.scaled(spec, dtype="f32")
     t0 = time.time()
     w = wl.make(spec)
     T, B = w.T, spec.B
@@ -330,6 +337,9 @@ def main() -> int:
     k1_avg_s = float(k1_ms.mean()) * 1e-3
     flops_per_launch = 2.0 * spec.d * spec.V * T          # algorithmic: 2*d*V per token
     achieved = flops_per_launch / k1_avg_s / 1e12
+    # fp32 inputs: six bf16 piece products per fp32 product are what the matrix cores execute
+    executed = achieved * (6.0 * ((spec.d + 31) // 32 * 32) / spec.d if f32 else 1.0)
+    peak = FP32_MFMA_PEAK_TFLOPS if f32 else BF16_MFMA_PEAK_TFLOPS
 
     traffic = recorded_traffic()
 
@@ -342,12 +352,12 @@ def main() -> int:
         zero = gpu.egtp_mfma_probe(sc.ctx, sink, 60000, False, 6)
         probe = {"what": "register-only 16x16x32 bf16 MFMA loop, one wave per SIMD, 1024 workgroups",
                  "random_operands_tflops": float(rnd[2:].mean()), "zero_operands_tflops": float(zero[2:].mean()),
-                 "achieved_over_random": achieved / float(rnd[2:].mean())}
+                 "achieved_over_random": executed / float(rnd[2:].mean())}
 
     # Context, not part of the path: what the vendor GEMM needs for hidden . W_lm^T of the same shape on the same
     # box when the [T x V] logits are written to HBM in bf16 (the tensor this path never writes).
     lib_gemm = None
-    if args.library_gemm:
+    if args.library_gemm and not f32:
         w_dev = w_lm_dev
         logits = torch.empty(T, spec.V, dtype=torch.bfloat16, device="cuda")
         for _ in range(2):
@@ -379,22 +389,24 @@ def main() -> int:
                          f"{cdt:.1f}s"}
 
     line = {
-        "metric": f"tokens scored/sec (EGTP prefill, d={spec.d} V={spec.V}) + % bf16 MFMA peak",
+        "metric": f"tokens scored/sec (EGTP prefill, d={spec.d} V={spec.V}) + % " + ("fp32" if f32 else "bf16") + " MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: EGTP prefill, {B} ragged sequences, {T} tokens, d={spec.d}, "
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}{' with fp32 inputs' if f32 else ''}: EGTP prefill, {B} ragged sequences, {T} tokens, d={spec.d}, "
                                f"V={spec.V}, head {spec.d}->{spec.d_h}->1, seed {spec.seed}",
                    "B": B, "T": T, "d": spec.d, "V": spec.V, "d_h": spec.d_h},
-        "pct_bf16_mfma_peak_whole_step": 100.0 * flops_per_launch / (ms_per_step * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+        ("pct_fp32_mfma_peak_whole_step" if f32 else "pct_bf16_mfma_peak_whole_step"):
+            100.0 * flops_per_launch / (ms_per_step * 1e-3) / 1e12 / peak,
         "roofline": {"kernel": "k1_entropy_bf16 (fused LM-head + entropy)", "bound": "mfma", "achieved": achieved,
-                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": traffic if args.workload == "serving" else None,
+                     "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "executed_bf16_tflops": executed, "executed_frac_of_bf16_peak": executed / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": traffic if args.workload == "serving" and not f32 else None,
                      "traffic_source": ("profiles/k1_entropy_bf16_serving_hbm_traffic.txt (rocprofv3 FETCH_SIZE + "
                                         "WRITE_SIZE passes of an earlier run of this kernel; replayed while the kernel "
                                         "and launch-plan sources hash to the recorded value, not measured in this run)")
-                     if traffic is not None and args.workload == "serving" else None,
-                     "frac_of_measured_mfma_rate": (achieved / probe["random_operands_tflops"]) if probe else None,
+                     if traffic is not None and args.workload == "serving" and not f32 else None,
+                     "frac_of_measured_mfma_rate": (executed / probe["random_operands_tflops"]) if probe else None,
                      "avg_launch_ms": k1_avg_s * 1e3, "min_launch_ms": float(k1_ms.min()),
                      "max_launch_ms": float(k1_ms.max()), "launches": int(k1_ms.size)},
         "mfma_probe": probe,
