@@ -105,6 +105,67 @@ def test_fp32_inputs_keep_every_mantissa_bit(gpu, side):
     assert err <= 2e-5, err
 
 
+@pytest.mark.parametrize("case", range(6))
+def test_fp32_seeded_random_shapes_against_the_oracle(gpu, case):
+    """fp32 hidden states and weights at seeded shapes: hidden sizes that are multiples of 4 but (mostly) not
+    of 32, so the six K segments carry zero padding; several vocabulary tiles and ragged token blocks; W_lm
+    packed up front or by the call itself.  Entropies to fp32 grade, the rest at the stated bars."""
+    rng = np.random.default_rng(5000 + case)
+    B = int(rng.integers(1, 7))
+    lens = tuple(int(x) for x in np.where(rng.random(B) < 0.15, 0, rng.integers(1, 300, size=B)))
+    d = 4 * int(rng.integers(1, 90))
+    V = int(rng.integers(1, 3000))
+    alpha = float(rng.choice([0.5, 1.0, 2.5]))
+    w = wl.make(wl.scaled(wl.SPECS["tiny"], seed=5100 + case, B=B, d=d, V=V, d_h=int(rng.integers(1, 50)),
+                          lengths=lens))
+    assert w.hidden.dtype == np.float32 and w.w_lm.dtype == np.float32
+    got = _run(gpu, w, alpha=alpha, pack_w_lm=bool(case % 2))
+    want = oracle.egtp(w.hidden, oracle.offsets_from_lengths(lens), w.w_lm, oracle.Head(w.w1, w.w2), alpha)
+    assert_egtp_close(got, want)
+    if want.entropy.size:
+        assert np.abs(got["entropy"] - want.entropy).max() <= 2e-5
+
+
+def test_fp32_plp_steps_and_a_context_on_the_packed_copy_alone(gpu):
+    """fp32 inputs through the decode path (one-token folds, Eq. 8) on a context that was created without the
+    row-major W_lm and lives on a packed copy made by another context of the same shape."""
+    import torch
+    lens = (5, 40, 1, 0, 77)
+    w = wl.make(wl.scaled(wl.SPECS["tiny"], seed=5200, B=len(lens), d=100, V=1300, d_h=20, lengths=lens))
+    gen = [wl.decode_hidden(w.spec, t + 1) for t in range(3)]
+    assert gen[0].dtype == np.float32
+    td = gpu.to_device
+    packer = _scorer(gpu, w)                                            # packs W_lm at creation
+    head = gpu.make_head(td(w.w1), td(w.w2))
+    cfg = gpu.egtp_config()
+    cfg.d, cfg.vocab, cfg.dtype, cfg.w_lm, cfg.alpha, cfg.head_len = 100, 1300, gpu.EGTP_F32, None, 1.0, head
+    ctx = gpu.egtp_create(cfg)
+    try:
+        assert gpu.egtp_packed_w_lm_bytes(ctx) == packer._w_packed.numel() == 6 * 128 * 2 * 6 * 256   # 6 row tiles x 6 segments of 128
+        gpu.egtp_adopt_packed_w_lm(ctx, packer._w_packed)
+        B, T = len(lens), w.T
+        ws = torch.empty(gpu.egtp_workspace_bytes(ctx, T, B), dtype=torch.uint8, device="cuda")
+        off = torch.from_numpy(oracle.offsets_from_lengths(lens)).cuda()
+        ent = torch.empty(T, dtype=torch.float32, device="cuda")
+        pooled = torch.empty(B, 100, dtype=torch.float32, device="cuda")
+        lse = torch.empty(B, dtype=torch.float32, device="cuda")
+        pred = torch.empty(B, dtype=torch.float32, device="cuda")
+        gpu.egtp_score(ctx, td(w.hidden), off, None, B, T, ws, ent, pooled, lse, pred)
+        want = oracle.plp(w.hidden, oracle.offsets_from_lengths(lens), gen, w.w_lm, oracle.Head(w.w1, w.w2))
+        for t, g in enumerate(gen):
+            e1 = torch.empty(B, dtype=torch.float32, device="cuda")
+            gpu.plp_step(ctx, td(g), None, None, None, B, B, pooled, lse, ws, e1, pred)
+            r = want[t]
+            new_tok = oracle.offsets_from_lengths(np.asarray(lens) + t + 1)[1:] - 1
+            assert np.abs(e1.cpu().numpy() - r.entropy[new_tok]).max() <= 2e-5
+            for b in range(B):
+                assert rel_l2(pooled[b].cpu().numpy(), r.pooled[b]) <= TOL_POOLED_REL_L2
+            assert np.abs(lse.cpu().numpy() - r.lse).max() <= TOL_LSE_ABS
+            assert_pred_close(pred.cpu().numpy(), r.pred)
+    finally:
+        gpu.egtp_destroy(ctx)
+
+
 def test_offsets_and_segment_ids_bit_exact(gpu):
     w = wl.make(wl.SPECS["tiny"])
     sc = _scorer(gpu, w)
