@@ -17,7 +17,7 @@ struct egtp_ctx {
     hipEvent_t *prof_events;  // 2 * prof_cap events, or NULL
     int prof_cap;
     int prof_count;
-    // packed copy of W_lm for the bf16 matrix-core kernel (caller's memory), or NULL
+    // packed copy of W_lm for the matrix-core kernel (caller's memory), or NULL
     const void *w_packed;
     // this device's copy of the library's static scratch array (plp_step_static)
     void *static_scratch;
@@ -52,7 +52,7 @@ struct Carver {
 struct Workspace {
     float *entropy;      // [T]
     float *k1_part;      // partial triples
-    int *k1_pace;        // pacing counters of the bf16 kernel
+    int *k1_pace;        // pacing counters of the fused kernel
     int32_t *unit_start; // [B+1]
     float *lse_new;      // [B]
     float *state_scale;  // [B]
@@ -73,8 +73,8 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     const size_t act_len = head_act_floats_bound(c.d, c.head_len.d_h, B);
     const size_t act_rem = head_act_floats_bound(c.d, c.head_rem.d_h, B);
     w.entropy = cv.take<float>((size_t)T);
-    w.k1_part = cv.take<float>(k1_partial_floats_bound(c.dtype, T, c.d, c.vocab));
-    w.k1_pace = cv.take<int>(k1_pace_ints_bound(c.dtype, T, c.d, c.vocab));
+    w.k1_part = cv.take<float>(k1_partial_floats_bound(T));
+    w.k1_pace = cv.take<int>(k1_pace_ints_bound(T));
     w.unit_start = cv.take<int32_t>((size_t)B + 1);
     w.lse_new = cv.take<float>((size_t)B);
     w.state_scale = cv.take<float>((size_t)B);

@@ -72,7 +72,7 @@ K1Plan k1_plan(int dtype, int64_t T, int d, int V)
 
 size_t k1_partial_floats(const K1Plan &p, int64_t T) { return (size_t)3 * (size_t)p.nsplit * (size_t)T; }
 
-size_t k1_partial_floats_bound(int /*dtype*/, int64_t T, int /*d*/, int /*V*/)
+size_t k1_partial_floats_bound(int64_t T)
 {
     // nsplit(T') <= target / ntb(T') + 1 + NSPLIT_SLACK, so
     // nsplit(T') * T' <= (target + (1 + NSPLIT_SLACK) * ntb(T')) * tb_tokens for every T' <= T
@@ -82,7 +82,7 @@ size_t k1_partial_floats_bound(int /*dtype*/, int64_t T, int /*d*/, int /*V*/)
     return (size_t)3 * (size_t)((target + (1 + NSPLIT_SLACK) * ntb) * tbk);
 }
 
-size_t k1_pace_ints_bound(int /*dtype*/, int64_t T, int /*d*/, int /*V*/)
+size_t k1_pace_ints_bound(int64_t T)
 {
     // units(T') = ntb(T') * nsplit(T') <= target + (1 + NSPLIT_SLACK) * ntb(T)
     const int64_t tbk = TB;

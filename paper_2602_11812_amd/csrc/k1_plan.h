@@ -44,12 +44,12 @@ struct K1Plan {
 K1Plan k1_plan(int dtype, int64_t T, int d, int V);
 // floats needed for the partial triples of a plan (3 * nsplit * T)
 size_t k1_partial_floats(const K1Plan &p, int64_t T);
-// upper bound of k1_partial_floats over every T' <= T
-size_t k1_partial_floats_bound(int dtype, int64_t T, int d, int V);
+// upper bound of k1_partial_floats over every T' <= T, whatever the shapes
+size_t k1_partial_floats_bound(int64_t T);
 // The kernel paces the workgroups that share an XCD with one counter per cohort of 32:
 // cohorts per XCD for a grid of `units` workgroups, and ints to reserve for every T' <= T.
 EGTP_HOST_DEVICE inline int k1_pace_cohorts(long units) { return (int)(((units + 7) / 8 + 31) / 32); }
-size_t k1_pace_ints_bound(int dtype, int64_t T, int d, int V);
+size_t k1_pace_ints_bound(int64_t T);
 
 // A range has a pacing point after every K1_PACE_TILES vocabulary tiles, so only
 // ranges longer than that pace at all.

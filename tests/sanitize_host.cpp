@@ -312,8 +312,8 @@ void plan_checks()
                 worst_part = part > worst_part ? part : worst_part;
                 worst_pace = pace > worst_pace ? pace : worst_pace;
                 // a workspace sized for T serves every smaller batch: the bounds cover the worst seen so far
-                CHECK(k1_partial_floats_bound(dtype, T, 4096, V) >= worst_part);
-                CHECK(k1_pace_ints_bound(dtype, T, 4096, V) >= worst_pace);
+                CHECK(k1_partial_floats_bound(T) >= worst_part);
+                CHECK(k1_pace_ints_bound(T) >= worst_pace);
             };
             for (int64_t T = 1; T <= 6000; ++T)
                 one(T);

@@ -866,6 +866,49 @@ def test_plp_steps_replayed_from_a_graph(gpu):
         assert bool(torch.isfinite(scratch))
 
 
+def test_paced_score_replayed_from_a_graph(gpu):
+    """The prefill call with the cohort pacing on (its counters are cleared by a kernel, not by a memset
+    node) captured in a HIP graph together with the offset scan: four replays, eager work and a poisoned
+    workspace in between, each bit-identical to the eager call."""
+    import torch
+    w = _small_bf16(seed=211, B=9, d=32, V=128037, d_h=24, lengths=(400, 731, 290, 1, 512, 640, 77, 333, 516))
+    assert gpu.egtp_launch_plan_query(gpu.EGTP_BF16, 32, 128037, w.T).paced == 1
+    sc = _scorer(gpu, w)
+    B, T, d = len(w.lengths), w.T, w.spec.d
+    hd = gpu.to_device(w.hidden)
+    lengths = torch.from_numpy(np.asarray(w.lengths, dtype=np.int32)).cuda()
+
+    def outputs():
+        return (torch.empty(B + 1, dtype=torch.int32, device="cuda"), torch.empty(T, dtype=torch.float32, device="cuda"),
+                torch.empty(B, d, dtype=torch.float32, device="cuda"), torch.empty(B, dtype=torch.float32, device="cuda"),
+                torch.empty(B, dtype=torch.float32, device="cuda"))
+
+    ws = sc.workspace(T, B)
+    eager = outputs()
+    gpu.egtp_build_offsets(sc.ctx, lengths, B, eager[0], None, T)      # also the warm-up outside the capture
+    gpu.egtp_score(sc.ctx, hd, eager[0], None, B, T, ws, *eager[1:])
+    torch.cuda.synchronize()
+    want = [t.clone() for t in eager]
+    got = outputs()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            gpu.egtp_build_offsets(sc.ctx, lengths, B, got[0], None, T)
+            gpu.egtp_score(sc.ctx, hd, got[0], None, B, T, ws, *got[1:])
+    torch.cuda.synchronize()
+    for replay in range(4):
+        ws.fill_(0xff)                                                    # NaN patterns everywhere, counters included
+        for t in got[1:]:
+            t.fill_(float("nan"))
+        graph.replay()
+        scratch = torch.randn(1 << 16, device="cuda").sum()              # unrelated eager work between replays
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), replay
+        assert bool(torch.isfinite(scratch))
+
+
 @pytest.mark.parametrize("case", range(12))
 def test_seeded_random_shapes_against_the_oracle(gpu, case):
     """Twelve seeded draws of batch size, ragged lengths (empty sequences included), hidden size,
