@@ -70,8 +70,8 @@ Workspace carve(const egtp_ctx *ctx, void *base, int64_t T, int32_t B)
     Workspace w;
     // layer 1 leaves more planes when a head has fewer row tiles, so a narrower head can need more
     // floats than a wider one: the larger of the two bounds, not the bound of the larger width
-    const size_t act_len = head_act_floats_bound(c.d, c.head_len.d_h, B);
-    const size_t act_rem = head_act_floats_bound(c.d, c.head_rem.d_h, B);
+    const size_t act_len = head_act_floats_bound(c.d, c.head_len.d_h, B, c.head_len.wdtype);
+    const size_t act_rem = head_act_floats_bound(c.d, c.head_rem.d_h, B, c.head_rem.wdtype);
     w.entropy = cv.take<float>((size_t)T);
     w.k1_part = cv.take<float>(k1_partial_floats_bound(T));
     w.k1_pace = cv.take<int>(k1_pace_ints_bound(T));
@@ -703,7 +703,7 @@ TrainWorkspace carve_train(void *base, int32_t B, int32_t d, int32_t d_h, int32_
 {
     Carver cv(base);
     TrainWorkspace w;
-    w.act_part = cv.take<float>(head_act_floats_bound(d, d_h, B));
+    w.act_part = cv.take<float>(head_act_floats_bound(d, d_h, B, DT_F32));
     w.act = cv.take<float>((size_t)B * (size_t)d_h);
     w.dact = cv.take<float>((size_t)B * (size_t)d_h);
     w.dz = cv.take<float>((size_t)B * (size_t)K);

@@ -109,6 +109,111 @@ __global__ __launch_bounds__(256) void head_layer1_kernel(const float *__restric
     }
 }
 
+// Layer 1 for at most SK_SEQS sequences and fp32 weights (a training batch, a handful of requests): the work is
+// one pass over W1, so the kernel is built around streaming it.  Workgroup = 16 head rows x one slice of at most
+// SK_SLICE elements of d; the slice of all pooled vectors sits in LDS (zero rows for missing sequences).  A wave
+// owns 4 rows; lane l takes K elements 4l .. 4l+3 of every 256: one 16-byte load per row, sixteen 16-byte LDS
+// reads, 256 FMAs into 4 x 16 accumulators.  The 64 accumulators are then summed over the 64 lanes by a halving
+// butterfly (a lane passes on the half it does not keep: 63 exchanges instead of 384), which leaves lane l with
+// the total of (row l / 16, sequence l % 16).  Fixed order: bit-reproducible.
+constexpr int SK_SEQS = 16, SK_SLICE = 512, SK_ROWS = 16;
+
+__global__ __launch_bounds__(256) void head_layer1_skinny_kernel(const float *__restrict__ x,
+                                                                 const int32_t *__restrict__ slot, int B, int d,
+                                                                 int d_h, const float *__restrict__ w1, int kchunk,
+                                                                 float *__restrict__ act_part)
+{
+    __shared__ __align__(16) float xs[SK_SEQS][SK_SLICE];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int kbeg = blockIdx.y * kchunk;
+    const int klen = min(d - kbeg, kchunk);  // a multiple of 4; <= 0 past the end of d: the plane is zeros
+    // lane b learns the state row of sequence b (asked for first: the counter of outstanding loads is in order)
+    int my_row = lane < B ? lane : 0;
+    if (slot)
+        my_row = slot[my_row];
+    // this lane's share of W1 next -- all of it in flight at once: a load per pass would be as many HBM
+    // latencies in a row
+    const int j0 = blockIdx.x * SK_ROWS + wave * 4;
+    constexpr int PASSES = SK_SLICE / 256;
+    float4 wv[PASSES][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int j = j0 + r < d_h ? j0 + r : d_h - 1;  // clamped rows are computed and dropped
+        const float *wrow = w1 + (long)j * d + (klen > 0 ? kbeg : 0);
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            // pieces past the end of the slice: load piece 0 instead (no branch around a load, so that the
+            // loads stay countable and the waits below can be exact); the staged vectors are zero there
+            const int k = 4 * lane + 256 * p;
+            wv[p][r] = *(const float4 *)(wrow + (k < klen ? k : 0));
+        }
+    }
+    // meanwhile stage the slice of the pooled vectors, every thread the same 16-byte piece of several rows.  All
+    // its loads are issued before the first store (addresses are clamped, not branched on: a wait per row
+    // would be sixteen cache latencies in a row); rows and pieces that do not exist become zeros.
+    constexpr int PIECES = SK_SLICE / 4;      // 16-byte pieces per staged row
+    constexpr int ROWS_AT_ONCE = 256 / PIECES;  // rows the 256 threads cover in one go
+    static_assert(256 % PIECES == 0 && PIECES % 64 == 0 && SK_SEQS % ROWS_AT_ONCE == 0, "staging layout");
+    const int pc = tid % PIECES;
+    const int brow = __builtin_amdgcn_readfirstlane(tid / PIECES);  // the same for a whole wave
+    const bool piece_ok = 4 * pc < klen;
+    const long piece = piece_ok ? (long)kbeg + 4 * pc : 0;
+    float4 xv16[SK_SEQS / ROWS_AT_ONCE];
+#pragma unroll
+    for (int i = 0; i < SK_SEQS / ROWS_AT_ONCE; ++i) {
+        // sequences past B read the row of sequence 0 (lane b of my_row holds 0 for them)
+        const long xrow = __builtin_amdgcn_readlane(my_row, brow + ROWS_AT_ONCE * i);
+        xv16[i] = *(const float4 *)(x + xrow * (long)d + piece);
+    }
+#pragma unroll
+    for (int i = 0; i < SK_SEQS / ROWS_AT_ONCE; ++i) {
+        const int b = brow + ROWS_AT_ONCE * i;
+        const bool ok = piece_ok && b < B;
+        float4 v = xv16[i];
+        v.x = ok ? v.x : 0.f, v.y = ok ? v.y : 0.f, v.z = ok ? v.z : 0.f, v.w = ok ? v.w : 0.f;
+        *(float4 *)&xs[b][4 * pc] = v;
+    }
+    __syncthreads();
+
+    float acc[64];  // acc[16 * r + b]
+#pragma unroll
+    for (int i = 0; i < 64; ++i)
+        acc[i] = 0.f;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int k = 4 * lane + 256 * p;  // past klen: the staged vectors are zero
+#pragma unroll
+        for (int b = 0; b < SK_SEQS; ++b) {
+            const float4 xv = *(const float4 *)&xs[b][k];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float a = acc[16 * r + b];
+                a = fmaf(wv[p][r].x, xv.x, a);
+                a = fmaf(wv[p][r].y, xv.y, a);
+                a = fmaf(wv[p][r].z, xv.z, a);
+                a = fmaf(wv[p][r].w, xv.w, a);
+                acc[16 * r + b] = a;
+            }
+        }
+    }
+    // halving butterfly over the lanes: after the step with distance o a lane holds n / 2 sums, the upper half
+    // of the indices if its bit o is set
+#pragma unroll
+    for (int o = 32, n = 64; o >= 1; o >>= 1, n >>= 1) {
+        const bool upper = (lane & o) != 0;
+#pragma unroll
+        for (int i = 0; i < n / 2; ++i) {
+            const float keep = upper ? acc[i + n / 2] : acc[i];
+            const float pass = upper ? acc[i] : acc[i + n / 2];
+            acc[i] = keep + __shfl_xor(pass, o);
+        }
+    }
+    const int b = lane & 15, j = j0 + (lane >> 4);
+    if (b < B && j < d_h)
+        act_part[((long)blockIdx.y * B + b) * d_h + j] = acc[0];
+}
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
@@ -370,8 +475,17 @@ __global__ __launch_bounds__(256) void head_layer2_kernel(const float *__restric
 
 }  // namespace
 
-int head_k_splits(int d, int d_h, int32_t B)
+// slices of the skinny kernel: as few as keep a slice within its LDS buffer
+static int skinny_slices(int d) { return (d + SK_SLICE - 1) / SK_SLICE; }
+static bool skinny_serves(int d, int32_t B, int wdtype)
 {
+    return wdtype == DT_F32 && B <= SK_SEQS && d % 4 == 0 && skinny_slices(d) <= 64;
+}
+
+int head_k_splits(int d, int d_h, int32_t B, int wdtype)
+{
+    if (skinny_serves(d, B, wdtype))
+        return skinny_slices(d);
     int base = (d + 511) / 512;  // slices of at most 512 along d ...
     base = base < 1 ? 1 : (base > 8 ? 8 : base);
     const long tiles = (long)((d_h + TM - 1) / TM) * ((B + TN - 1) / TN);
@@ -382,16 +496,19 @@ int head_k_splits(int d, int d_h, int32_t B)
     return n < 1 ? 1 : (int)n;
 }
 
-size_t head_act_floats_bound(int d, int d_h, int32_t B)
+size_t head_act_floats_bound(int d, int d_h, int32_t B, int wdtype)
 {
-    // the number of planes only depends on how many 64-sequence tiles the batch has
+    // the number of planes only depends on how many 64-sequence tiles the batch has -- and, for fp32 weights,
+    // on whether the batch is small enough for the skinny kernel
     size_t best = 0;
     for (int32_t st = 1; st <= (B + TN - 1) / TN; ++st) {
         const int32_t b = st * TN < B ? st * TN : B;
-        const size_t f = (size_t)head_k_splits(d, d_h, b) * (size_t)b * (size_t)d_h;
+        const size_t f = (size_t)head_k_splits(d, d_h, b, wdtype) * (size_t)b * (size_t)d_h;
         best = f > best ? f : best;
     }
-    return best;
+    const int32_t bs = B < SK_SEQS ? B : SK_SEQS;
+    const size_t fs = (size_t)head_k_splits(d, d_h, bs, wdtype) * (size_t)bs * (size_t)d_h;
+    return fs > best ? fs : best;
 }
 
 hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, int d_h, const void *w1,
@@ -399,7 +516,17 @@ hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, in
 {
     if (B <= 0)
         return hipSuccess;
-    const int nks = head_k_splits(d, d_h, B);
+    const int nks = head_k_splits(d, d_h, B, wdtype);
+    if (skinny_serves(d, B, wdtype)) {
+        // whole 256-element passes; nks = ceil(d / SK_SLICE) keeps a slice within the LDS buffer and leaves no
+        // slice empty (a slice past the end of d would still write its plane: zeros)
+        const int kchunk_s = ((d + nks - 1) / nks + 255) / 256 * 256;
+        if (kchunk_s > SK_SLICE)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(head_layer1_skinny_kernel, dim3((d_h + SK_ROWS - 1) / SK_ROWS, nks), dim3(256), 0, st, x, slot,
+                           B, d, d_h, (const float *)w1, kchunk_s, act_part);
+        return hipGetLastError();
+    }
     const dim3 grid((d_h + TM - 1) / TM, (B + TN - 1) / TN, nks);
     if (wdtype == DT_BF16 && d % 8 == 0) {
         // matrix-core path: slices are multiples of the MFMA K step (late slices may be empty
@@ -427,7 +554,7 @@ hipError_t head_forward(const HeadArgs &a, hipStream_t st)
 {
     if (a.B <= 0)
         return hipSuccess;
-    const int nks = head_k_splits(a.d, a.d_h, a.B);
+    const int nks = head_k_splits(a.d, a.d_h, a.B, a.wdtype);
     const size_t lds2 = ((size_t)a.d_h + 4 * (size_t)a.n_out) * sizeof(float);
     if (lds2 > 96 * 1024)
         return hipErrorInvalidValue;

@@ -316,7 +316,7 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     hipError_t e = head_layer1(a.x, nullptr, a.B, a.d, a.d_h, a.w1, DT_F32, a.act_part, st);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(train_sample_kernel, dim3(a.B), dim3(256), lds, st, a.act_part, head_k_splits(a.d, a.d_h, a.B), a.B,
+    hipLaunchKernelGGL(train_sample_kernel, dim3(a.B), dim3(256), lds, st, a.act_part, head_k_splits(a.d, a.d_h, a.B, DT_F32), a.B,
                        a.d_h, a.K, a.b1, a.w2, a.b2, a.centers, a.bin, a.y, a.steps, a.n_seqs, a.lambda, a.act,
                        a.dact, a.dz, a.loss_part);
     Adam h;

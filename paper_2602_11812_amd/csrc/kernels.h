@@ -107,17 +107,18 @@ struct HeadArgs {
     const void *w1; const float *b1;
     const void *w2; const float *b2;
     const float *bin_centers; // [n_out] when n_out > 1
-    float *act;               // workspace, head_act_floats_bound(d, d_h, B) floats: partial pre-activations
+    float *act;               // workspace, head_act_floats_bound(d, d_h, B, wdtype) floats: partial pre-activations
     float *pred;              // [B]
     float *p_hat;             // [B x n_out] softmax over the bins (Eq. 6), or NULL; n_out > 1 only
 };
 // Number of partial pre-activation planes layer 1 leaves: it is split along d so that about a
-// thousand workgroups exist whatever the batch (a small batch gets many thin slices).
-int head_k_splits(int d, int d_h, int32_t B);
+// thousand workgroups exist whatever the batch (a small batch gets many thin slices); a small batch on fp32
+// weights is served by a kernel of its own that leaves one plane per 512 elements of d.
+int head_k_splits(int d, int d_h, int32_t B, int wdtype);
 // floats of partial planes sufficient for every batch of at most B sequences
-size_t head_act_floats_bound(int d, int d_h, int32_t B);
+size_t head_act_floats_bound(int d, int d_h, int32_t B, int wdtype);
 hipError_t head_forward(const HeadArgs &a, hipStream_t st);
-// layer 1 alone: partial pre-activations act_part[head_k_splits(d, d_h, B) x B x d_h] (no bias, no ReLU)
+// layer 1 alone: partial pre-activations act_part[head_k_splits(d, d_h, B, wdtype) x B x d_h] (no bias, no ReLU)
 hipError_t head_layer1(const float *x, const int32_t *slot, int32_t B, int d, int d_h, const void *w1,
                        int wdtype, float *act_part, hipStream_t st);
 
@@ -139,7 +140,7 @@ struct TrainArgs {
     float *g_w1, *g_b1, *g_w2, *g_b2;  // optional copies of the gradients
     float *loss;               // [3] total, CE part, MSE part
     // workspace
-    float *act_part;           // head_act_floats_bound(d, d_h, B) floats
+    float *act_part;           // head_act_floats_bound(d, d_h, B, DT_F32) floats
     float *act;                // [B x d_h]
     float *dact;               // [B x d_h]
     float *dz;                 // [B x K]

@@ -166,6 +166,36 @@ def test_fp32_plp_steps_and_a_context_on_the_packed_copy_alone(gpu):
         gpu.egtp_destroy(ctx)
 
 
+def test_fp32_head_small_batch_with_slots(gpu):
+    """fp32 head weights and at most 16 live sequences: the first head layer streams W1 slice by slice (three
+    slices of d = 2308, the last of 260 elements; d_h = 37 leaves a last group of 5 rows) and reads each
+    sequence's state through its slot."""
+    import torch
+    lens = (3, 0, 9, 1, 30, 2, 7)
+    w = wl.make(wl.scaled(wl.SPECS["tiny"], seed=5300, B=len(lens), d=2308, V=130, d_h=37, lengths=lens))
+    gen = [wl.decode_hidden(w.spec, t + 1) for t in range(2)]
+    sc = _scorer(gpu, w)
+    B, d, S = len(lens), 2308, 11
+    slot = np.array([10, 4, 0, 7, 2, 9, 5], dtype=np.int32)
+    slot_dev = torch.from_numpy(slot).cuda()
+    pooled = torch.zeros(S, d, dtype=torch.float32, device="cuda")
+    lse = torch.full((S,), -math.inf, dtype=torch.float32, device="cuda")
+    out = sc.score(gpu.to_device(w.hidden), _offsets_on_gpu(gpu, sc, lens))
+    want0 = oracle.egtp(w.hidden, oracle.offsets_from_lengths(lens), w.w_lm, oracle.Head(w.w1, w.w2))
+    assert_egtp_close(_np(out), want0)
+    pooled[slot_dev.long()] = out["pooled"]
+    lse[slot_dev.long()] = out["lse"]
+    want = oracle.plp(w.hidden, oracle.offsets_from_lengths(lens), gen, w.w_lm, oracle.Head(w.w1, w.w2))
+    for t, g in enumerate(gen):
+        pred = sc.step(gpu.to_device(g), pooled, lse, slot_dev=slot_dev)
+        r = want[t]
+        for b in range(B):
+            assert rel_l2(pooled[slot[b]].cpu().numpy(), r.pooled[b]) <= TOL_POOLED_REL_L2
+        assert_pred_close(pred.cpu().numpy(), r.pred)
+    untouched = np.setdiff1d(np.arange(S), slot)
+    assert bool((pooled[torch.from_numpy(untouched).cuda()] == 0).all())
+
+
 def test_offsets_and_segment_ids_bit_exact(gpu):
     w = wl.make(wl.SPECS["tiny"])
     sc = _scorer(gpu, w)

@@ -133,6 +133,13 @@ def test_one_step_ragged_shapes(gpu):
     _run_steps(gpu, ts, 1)
 
 
+def test_small_batch_ragged_slices_of_d(gpu):
+    # at most 16 samples: layer 1 streams W1 in slices of at most 1024 elements of d, 16 head rows per workgroup;
+    # d = 2308 leaves a last slice of 260 elements, d_h = 52 a last workgroup of 4 rows, B = 13 three empty columns
+    ts = wl.make_train(16, B=13, d=2308, d_h=52, K=11)
+    _run_steps(gpu, ts, 2)
+
+
 def test_several_steps_minibatches(gpu):
     ts = wl.make_train(12, B=64, d=128, d_h=200, K=20)
     _run_steps(gpu, ts, 6, batch=16)
