@@ -2,18 +2,19 @@
 // soft labels of Eq. 5, the joint loss of Eq. 7, the per-sequence step average of Eq. 9
 // (as a per-sample weight), the backward pass through the head only, and AdamW.
 //
-// Everything is fp32 (master weights, moments, activations).  The sequence of kernels:
+// Everything is fp32 (master weights, moments, activations).  Three launches:
 //   1. layer 1 forward     partial pre-activations, split along d   (shared with scoring)
 //   2. per-sample kernel   ReLU, logits, softmax, expected value, soft label, the two loss
 //                          terms, d loss / d logits and d loss / d pre-activation
-//   3. small parameters    gradient of W2, b2 and b1 reduced over the batch in a fixed order,
-//                          AdamW applied in the same thread
-//   4. W1                  gradient tile [64 x 64] of  dact^T . x  accumulated over the batch in
+//   3. the updates, one grid of three kinds of workgroups that only need what 2. left behind:
+//      W1                  gradient tile [64 x 64] of  dact^T . x  accumulated over the batch in
 //                          registers and consumed by AdamW on the spot -- the d_h x d gradient
 //                          is never written unless the caller asks for a copy.  With the
-//                          paper's batch of 16 this kernel is a pure stream over W1 and its two
+//                          paper's batch of 16 this part is a pure stream over W1 and its two
 //                          moments (read and written once each).
-//   5. loss                fixed-order sum of the per-sample terms (one more workgroup of launch 3)
+//      small parameters    gradient of W2, b2 and b1 reduced over the batch in a fixed order,
+//                          AdamW applied in the same thread
+//      loss                fixed-order sum of the per-sample terms (the last workgroup)
 // No floating-point atomics anywhere: results are bit-reproducible.
 #include "kernels.h"
 #include "partial_planes.h"
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(256) void train_sample_kernel(
 }
 
 // ---- 5. loss = {lambda CE + (1 - lambda) MSE, CE, MSE}, fixed summation order -----------------
-// (one workgroup of 256 threads; runs as the last workgroup of the small-parameter kernel)
+// (one workgroup of 256 threads; runs as the last workgroup of the update launch)
 __device__ void sum_loss(const float *__restrict__ loss_part, int B, float lambda, float *__restrict__ loss)
 {
     __shared__ float red[2][256];
@@ -178,19 +179,15 @@ __device__ void sum_loss(const float *__restrict__ loss_part, int B, float lambd
     }
 }
 
-// ---- 3. W2, b2, b1: one thread per parameter ----------------------------------------------
-__global__ __launch_bounds__(256) void train_small_update_kernel(
-    const float *__restrict__ act, const float *__restrict__ dact, const float *__restrict__ dz, int B, int d_h,
-    int K, Adam h, float *__restrict__ w2, float *__restrict__ m_w2, float *__restrict__ v_w2,
+// ---- 3. W2, b2, b1: one thread per parameter (workgroup `block` of the small-parameter part) ----
+__device__ __forceinline__ void small_update(
+    int block, const float *__restrict__ act, const float *__restrict__ dact, const float *__restrict__ dz, int B,
+    int d_h, int K, const Adam &h, float *__restrict__ w2, float *__restrict__ m_w2, float *__restrict__ v_w2,
     float *__restrict__ b2, float *__restrict__ m_b2, float *__restrict__ v_b2, float *__restrict__ b1,
     float *__restrict__ m_b1, float *__restrict__ v_b1, float *__restrict__ g_w2, float *__restrict__ g_b2,
-    float *__restrict__ g_b1, const float *__restrict__ loss_part, float lambda, float *__restrict__ loss)
+    float *__restrict__ g_b1)
 {
-    if (blockIdx.x == gridDim.x - 1) {  // one extra workgroup: the loss of the batch (5.)
-        sum_loss(loss_part, B, lambda, loss);
-        return;
-    }
-    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    const long e = (long)block * 256 + threadIdx.x;
     const long n_w2 = (long)K * d_h;
     float g = 0.f;
     float *w, *m, *v, *gout;
@@ -226,15 +223,16 @@ constexpr int GM = 64;  // rows j of W1 per tile
 constexpr int GN = 64;  // columns k of W1 per tile
 constexpr int GB = 16;  // samples per LDS stage
 
-__global__ __launch_bounds__(256) void train_w1_update_kernel(
-    const float *__restrict__ x, const float *__restrict__ dact, int B, int d, int d_h, Adam h,
-    float *__restrict__ w1, float *__restrict__ m_w1, float *__restrict__ v_w1, float *__restrict__ g_w1)
+__device__ __forceinline__ void w1_update(
+    int tile_k, int tile_j, const float *__restrict__ x, const float *__restrict__ dact, int B, int d, int d_h,
+    const Adam &h, float *__restrict__ w1, float *__restrict__ m_w1, float *__restrict__ v_w1,
+    float *__restrict__ g_w1)
 {
     __shared__ __align__(16) float As[GB][GM];  // dact[b][j]
     __shared__ __align__(16) float Bs[GB][GN];  // x[b][k]
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    const int k0 = blockIdx.x * GN, j0 = blockIdx.y * GM;
+    const int k0 = tile_k * GN, j0 = tile_j * GM;
     const int lb = tid >> 4;        // sample row this thread stages
     const int lc = (tid & 15) * 4;  // first of its four columns
 
@@ -298,6 +296,34 @@ __global__ __launch_bounds__(256) void train_w1_update_kernel(
     }
 }
 
+// ---- 3. + 4. + 5. in one launch: all three need only what the per-sample kernel left behind and touch
+// disjoint parameters, so they share a grid.  The W1 tiles come first in launch order (they carry the
+// memory traffic of the step), then the workgroups of the small parameters, the loss last.
+struct UpdateArgs {
+    const float *x, *act, *dact, *dz, *loss_part;
+    int B, d, d_h, K;
+    int tiles_k, tiles_w1, blocks_small;
+    float lambda;
+    float *w1, *m_w1, *v_w1, *g_w1;
+    float *w2, *m_w2, *v_w2, *g_w2;
+    float *b2, *m_b2, *v_b2, *g_b2;
+    float *b1, *m_b1, *v_b1, *g_b1;
+    float *loss;
+};
+
+__global__ __launch_bounds__(256) void train_update_kernel(UpdateArgs a, Adam h)
+{
+    const int id = blockIdx.x;
+    if (id < a.tiles_w1) {
+        w1_update(id % a.tiles_k, id / a.tiles_k, a.x, a.dact, a.B, a.d, a.d_h, h, a.w1, a.m_w1, a.v_w1, a.g_w1);
+    } else if (id < a.tiles_w1 + a.blocks_small) {
+        small_update(id - a.tiles_w1, a.act, a.dact, a.dz, a.B, a.d_h, a.K, h, a.w2, a.m_w2, a.v_w2, a.b2, a.m_b2,
+                     a.v_b2, a.b1, a.m_b1, a.v_b1, a.g_w2, a.g_b2, a.g_b1);
+    } else {
+        sum_loss(a.loss_part, a.B, a.lambda, a.loss);
+    }
+}
+
 }  // namespace
 
 hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
@@ -329,13 +355,25 @@ hipError_t head_train_step(const TrainArgs &a, hipStream_t st)
     h.wd = a.weight_decay;
     h.corr1 = a.corr1;
     h.corr2 = a.corr2;
+    // the parameter updates come last: the forward and the backward pass above read the old W1 / W2
+    UpdateArgs u;
+    u.x = a.x, u.act = a.act, u.dact = a.dact, u.dz = a.dz, u.loss_part = a.loss_part;
+    u.B = a.B, u.d = a.d, u.d_h = a.d_h, u.K = a.K;
+    u.lambda = a.lambda;
+    u.w1 = a.w1, u.m_w1 = a.m_w1, u.v_w1 = a.v_w1, u.g_w1 = a.g_w1;
+    u.w2 = a.w2, u.m_w2 = a.m_w2, u.v_w2 = a.v_w2, u.g_w2 = a.g_w2;
+    u.b2 = a.b2, u.m_b2 = a.m_b2, u.v_b2 = a.v_b2, u.g_b2 = a.g_b2;
+    u.b1 = a.b1, u.m_b1 = a.m_b1, u.v_b1 = a.v_b1, u.g_b1 = a.g_b1;
+    u.loss = a.loss;
     const long n_small = (long)a.K * a.d_h + a.K + a.d_h;
-    hipLaunchKernelGGL(train_small_update_kernel, dim3((unsigned)((n_small + 255) / 256 + 1)), dim3(256), 0, st, a.act,
-                       a.dact, a.dz, a.B, a.d_h, a.K, h, a.w2, a.m_w2, a.v_w2, a.b2, a.m_b2, a.v_b2, a.b1, a.m_b1,
-                       a.v_b1, a.g_w2, a.g_b2, a.g_b1, a.loss_part, a.lambda, a.loss);
-    // W1 is last: the forward pass and the backward pass above read the old W1 / W2
-    hipLaunchKernelGGL(train_w1_update_kernel, dim3((a.d + GN - 1) / GN, (a.d_h + GM - 1) / GM), dim3(256), 0, st,
-                       a.x, a.dact, a.B, a.d, a.d_h, h, a.w1, a.m_w1, a.v_w1, a.g_w1);
+    const long tiles_k = (a.d + GN - 1) / GN, tiles_j = (a.d_h + GM - 1) / GM;
+    const long blocks_small = (n_small + 255) / 256;
+    if (tiles_k * tiles_j + blocks_small + 1 > 0x7fffffffL)
+        return hipErrorInvalidValue;
+    u.tiles_k = (int)tiles_k;
+    u.tiles_w1 = (int)(tiles_k * tiles_j);
+    u.blocks_small = (int)blocks_small;
+    hipLaunchKernelGGL(train_update_kernel, dim3((unsigned)(u.tiles_w1 + u.blocks_small + 1)), dim3(256), 0, st, u, h);
     return hipGetLastError();
 }
 
