@@ -67,13 +67,7 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
     torch.cuda.synchronize()
     if args.graph:
         # the decode loop as a HIP graph: the 16 distinct steps are captured once and replayed; the fused
-        # kernel is timed with events on 32 eager steps first (no events inside the capture)
-        gpu.egtp_profile_enable(sc.ctx, True, 32)
-        for i in range(32):
-            gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
-        torch.cuda.synchronize()
-        k1_ms = gpu.egtp_profile_read(sc.ctx)
-        gpu.egtp_profile_enable(sc.ctx, False)
+        # kernel is timed with events on 64 eager steps afterwards (no events inside the capture)
         side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
@@ -89,6 +83,12 @@ def bench_plp(args, gpu, wl, np, torch) -> int:
             graph.replay()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        gpu.egtp_profile_enable(sc.ctx, True, 64)
+        for i in range(64):
+            gpu.plp_step(sc.ctx, hs[i % 16], None, None, None, B, B, pooled, lse, ws, None, pred)
+        torch.cuda.synchronize()
+        k1_ms = gpu.egtp_profile_read(sc.ctx)
+        gpu.egtp_profile_enable(sc.ctx, False)
     else:
         gpu.egtp_profile_enable(sc.ctx, True, min(1024, steps))
         t0 = time.perf_counter()
